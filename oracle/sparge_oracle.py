@@ -1,0 +1,401 @@
+"""CPU oracle for SpargeAttn's hot path (test infrastructure, NOT a product path).
+
+Plain numpy, fp64 unless the text below says otherwise, one (batch, head) at a time, block by
+block, in the order and notation of the paper's Algorithm 1.  Nothing here is blocked, fused or
+re-ordered beyond what the algorithm states, and nothing is shared with the HIP kernels.
+Only tests, the smoke check and the benchmark's cpu_baseline leg may import this module.
+
+Notation (Sec. 3.1, Def. 1, Alg. 1): N tokens, head dim d, Q blocks of b_q = 128 rows, K/V blocks
+of b_k = 64 rows, T_m = ceil(N/b_q), T_n = ceil(N/b_k); c_w = 4 "warps" split a Q block into row
+groups I_w of 32 rows (Alg. 1 line 13).  Hyper-parameters tau, theta, lambda (Sec. 3.6).
+
+Readings of the paper where it is silent or ambiguous (each also listed in the design notes):
+  * CosSim (Sec. 3.2): mean cosine similarity over all ordered token pairs of a block (diagonal
+    included); a zero token has zero cosine with everything.  The literal printed formula
+    mean(XX^T/|max(XX^T)|) is available as cossim_blocks(..., literal=True) for comparison only.
+  * S-hat carries the 1/sqrt(d) softmax scale (it is a compressed version of P = softmax(QK^T/sqrt d)).
+  * TopCdf (Sec. 3.2): smallest descending prefix whose mass reaches tau * sum, i.e. an entry is kept
+    iff the mass ranked strictly before it is < tau * sum; ties rank by ascending block index;
+    entries with zero probability are never selected.
+  * Causal attention: blocks entirely in the future are -inf in S-hat and 0 in the mask, even under
+    the fix-block overrides; the K block that holds a Q block's first diagonal key is always kept.
+  * Partial last blocks: statistics over valid rows only.
+  * lambda test (Alg. 1 line 15): execute iff max over the row group's valid rows of
+    (m_local - m_ij) > lambda; l is always updated (line 13 precedes line 15).
+  * Quant (Alg. 1 line 3, SageAttention per-block INT8): symmetric, scale = amax/127, round half to
+    even, K smoothed by its per-head token mean.  The fp32 operation sequence is spelled out in
+    quantize_q / quantize_k and is part of the specification.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass
+from typing import Optional, Tuple
+
+import numpy as np
+
+BQ = 128
+BK = 64
+ROW_GROUP = 32  # b_q / c_w with c_w = 4
+NEG_INF = -np.inf
+DONT_CARE_EPS = 1e-5
+
+
+def nblocks(N: int, b: int) -> int:
+    return (N + b - 1) // b
+
+
+# ----------------------------------------------------------------------------------------------
+# Stage 1: predictor (Sec. 3.2, Alg. 1 lines 4-6)
+# ----------------------------------------------------------------------------------------------
+def pool_blocks(X: np.ndarray, b: int) -> np.ndarray:
+    """Block means over tokens (Alg. 1 line 4): X [N,d] -> [T,d]; a partial block averages its valid rows."""
+    X = np.asarray(X, dtype=np.float64)
+    T = nblocks(X.shape[0], b)
+    out = np.empty((T, X.shape[1]), dtype=np.float64)
+    for t in range(T):
+        out[t] = X[t * b:(t + 1) * b].mean(axis=0)
+    return out
+
+
+def cossim_blocks(X: np.ndarray, b: int, literal: bool = False) -> np.ndarray:
+    """Block self-similarity s = CosSim(X_t) (Alg. 1 line 5; Sec. 3.2): X [N,d] -> [T].
+
+    Default reading: normalise every token, form the b x b Gram matrix of cosines, take its mean.
+    literal=True evaluates the printed expression mean(XX^T / |max(XX^T)|) instead.
+    """
+    X = np.asarray(X, dtype=np.float64)
+    T = nblocks(X.shape[0], b)
+    out = np.empty(T, dtype=np.float64)
+    for t in range(T):
+        blk = X[t * b:(t + 1) * b]
+        if literal:
+            G = blk @ blk.T
+            mx = abs(G.max())
+            out[t] = (G / mx).mean() if mx > 0 else 0.0
+            continue
+        nrm = np.sqrt((blk * blk).sum(axis=1, keepdims=True))
+        unit = np.divide(blk, nrm, out=np.zeros_like(blk), where=nrm > 0)
+        out[t] = (unit @ unit.T).mean()
+    return out
+
+
+def block_causal_future(i: int, j: int) -> bool:
+    """True if K block j lies entirely after every row of Q block i (nothing in it may be attended)."""
+    return j * BK > i * BQ + (BQ - 1)
+
+
+def compressed_map(q: np.ndarray, k: np.ndarray, s_k: np.ndarray, theta: float, scale: float,
+                   causal: bool) -> np.ndarray:
+    """P-hat = row softmax of S-hat = scale * q k^T with -inf columns (Alg. 1 lines 5-6).
+
+    Columns of non-self-similar K blocks (s_k < theta) and, if causal, entirely-future blocks are
+    -inf.  A row without any finite entry is all zeros.
+    """
+    S = scale * (q @ k.T)
+    S[:, s_k < theta] = NEG_INF
+    if causal:
+        for i in range(S.shape[0]):
+            for j in range(S.shape[1]):
+                if block_causal_future(i, j):
+                    S[i, j] = NEG_INF
+    P = np.zeros_like(S)
+    for i in range(S.shape[0]):
+        row = S[i]
+        mx = row.max()
+        if mx == NEG_INF:
+            continue
+        e = np.exp(row - mx)
+        P[i] = e / e.sum()
+    return P
+
+
+def top_cdf(p: np.ndarray, tau: float) -> Tuple[np.ndarray, np.ndarray]:
+    """TopCdf(P-hat[i], tau) (Sec. 3.2).  Returns (mask, dont_care), both bool [n].
+
+    Rank entries by (value descending, index ascending); entry at rank r is kept iff the mass of
+    the entries ranked before it is < tau * sum(p) and its own value is > 0.
+    dont_care marks entries whose decision sits within 1e-5 of the threshold: either their
+    preceding mass is within 1e-5 of tau*sum, or their value is within 1e-5 (relative) of the
+    smallest kept value while lying on the other side of the cut.
+    """
+    n = p.shape[0]
+    order = np.lexsort((np.arange(n), -p))  # primary key -p, ties by index
+    sp = p[order]
+    total = sp.sum()
+    before = np.concatenate(([0.0], np.cumsum(sp)[:-1]))
+    keep_sorted = (before < tau * total) & (sp > 0)
+    mask = np.zeros(n, dtype=bool)
+    mask[order] = keep_sorted
+    dc_sorted = (np.abs(before - tau * total) <= DONT_CARE_EPS) & (sp > 0)
+    if keep_sorted.any():
+        p_cut = sp[keep_sorted].min()
+        near = np.abs(sp - p_cut) <= DONT_CARE_EPS * max(p_cut, 1e-30)
+        # values tied (to 1e-5) with the cut value: which of them fall before the cut depends on
+        # rounding of the ranking, unless all of them are on the same side
+        if near.any() and not (keep_sorted[near].all() or (~keep_sorted[near]).all()):
+            dc_sorted |= near
+    dont_care = np.zeros(n, dtype=bool)
+    dont_care[order] = dc_sorted
+    return mask, dont_care
+
+
+@dataclass
+class Prediction:
+    mask: np.ndarray        # uint8 [T_m, T_n], 1 = compute the block (M_g)
+    dont_care: np.ndarray   # bool  [T_m, T_n], decision within 1e-5 of a threshold
+    sim_q: np.ndarray       # [T_m]
+    sim_k: np.ndarray       # [T_n]
+    pooled_q: np.ndarray    # [T_m, d]
+    pooled_k: np.ndarray    # [T_n, d]
+    p_hat: np.ndarray       # [T_m, T_n]
+
+
+def predict(Q: np.ndarray, K: np.ndarray, tau: float, theta: float, scale: Optional[float] = None,
+            causal: bool = False) -> Prediction:
+    """Stage-1 block mask M_g of one head (Alg. 1 lines 4-6; Sec. 3.2, Eq. for M_g overrides)."""
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    N, d = Q.shape
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    q = pool_blocks(Q, BQ)
+    k = pool_blocks(K, BK)
+    s_q = cossim_blocks(Q, BQ)
+    s_k = cossim_blocks(K, BK)
+    P = compressed_map(q, k, s_k, theta, scale, causal)
+    Tm, Tn = P.shape
+    mask = np.zeros((Tm, Tn), dtype=bool)
+    dc = np.zeros((Tm, Tn), dtype=bool)
+    for i in range(Tm):
+        mask[i], dc[i] = top_cdf(P[i], tau)
+    # fix-block overrides: non-self-similar Q rows / K columns are always computed
+    fix_q = s_q < theta
+    fix_k = s_k < theta
+    mask[fix_q, :] = True
+    mask[:, fix_k] = True
+    dc[fix_q, :] = False
+    dc[:, fix_k] = False
+    # a similarity within 1e-5 of theta makes the row (Q) or the whole head (K) undecidable
+    near_q = np.abs(s_q - theta) <= DONT_CARE_EPS
+    near_k = np.abs(s_k - theta) <= DONT_CARE_EPS
+    dc[near_q, :] = True
+    if near_k.any():
+        dc[:, :] = True
+    if causal:
+        for i in range(Tm):
+            for j in range(Tn):
+                if block_causal_future(i, j):
+                    mask[i, j] = False
+                    dc[i, j] = False
+            jd = (i * BQ) // BK  # block holding the first row's own position
+            mask[i, jd] = True
+            dc[i, jd] = False
+    return Prediction(mask.astype(np.uint8), dc, s_q, s_k, q, k, P)
+
+
+# ----------------------------------------------------------------------------------------------
+# Quant (Alg. 1 line 3): per-block symmetric INT8, K smoothed by its token mean
+# ----------------------------------------------------------------------------------------------
+def _quant_blocks(X32: np.ndarray, b: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Per-block INT8 quantization of an fp32 matrix, fp32 arithmetic with these rounding points:
+    amax = max|x| over the block's valid rows; delta = fl32(amax/127);
+    x_hat = rint_half_even(fl32(fl32(127*x)/amax)); a zero block gives x_hat = 0, delta = 0."""
+    assert X32.dtype == np.float32
+    N = X32.shape[0]
+    T = nblocks(N, b)
+    Xq = np.zeros(X32.shape, dtype=np.int8)
+    delta = np.zeros(T, dtype=np.float32)
+    c127 = np.float32(127.0)
+    for t in range(T):
+        blk = X32[t * b:(t + 1) * b]
+        amax = np.float32(np.abs(blk).max())
+        if amax == 0:
+            continue
+        delta[t] = amax / c127
+        y = (c127 * blk) / amax  # two correctly rounded fp32 operations
+        assert y.dtype == np.float32
+        Xq[t * b:(t + 1) * b] = np.rint(y).astype(np.int8)  # rint: ties to even
+    return Xq, delta
+
+
+def quantize_q(Q: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """Q-hat, delta_Q per 128-row block.  Q holds 16-bit values, taken exactly into fp32."""
+    return _quant_blocks(np.asarray(Q, dtype=np.float32), BQ)
+
+
+def k_mean(K: np.ndarray) -> np.ndarray:
+    """Per-head token mean of K: the exactly rounded fp64 sum over tokens, divided by N in fp64,
+    then rounded to fp32."""
+    K = np.asarray(K, dtype=np.float64)
+    N, d = K.shape
+    s = np.array([math.fsum(K[:, c]) for c in range(d)], dtype=np.float64)
+    return (s / float(N)).astype(np.float32)
+
+
+def quantize_k(K: np.ndarray) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """K-hat, delta_K per 64-row block, and the mean that was removed: K' = fl32(K - mean)."""
+    mean = k_mean(K)
+    Ks = np.asarray(K, dtype=np.float32) - mean[None, :]
+    Kq, delta = _quant_blocks(Ks, BK)
+    return Kq, delta, mean
+
+
+# ----------------------------------------------------------------------------------------------
+# rounding to the 16-bit type that feeds the P~V product / holds the output
+# ----------------------------------------------------------------------------------------------
+def round16(x: np.ndarray, dtype: str) -> np.ndarray:
+    """Round fp64 values to fp16 or bf16 (nearest, ties to even), returned as fp64."""
+    if dtype == "fp16":
+        return np.asarray(x, dtype=np.float64).astype(np.float16).astype(np.float64)
+    if dtype == "bf16":
+        f = np.asarray(x, dtype=np.float64).astype(np.float32)
+        u = np.ascontiguousarray(f).view(np.uint32).astype(np.uint64)
+        r = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16) << 16
+        return r.astype(np.uint32).view(np.float32).astype(np.float64).reshape(f.shape)
+    if dtype == "none":
+        return np.asarray(x, dtype=np.float64)
+    raise ValueError(dtype)
+
+
+# ----------------------------------------------------------------------------------------------
+# Stage 2: sparse flash loop with the lambda skip (Alg. 1 lines 7-20; Sec. 3.1, 3.3, 3.4)
+# ----------------------------------------------------------------------------------------------
+@dataclass
+class AttnResult:
+    O: np.ndarray            # fp64 [N, d]: O_i = diag(l)^-1 O_ij, not rounded
+    qk_tiles: int            # Q_iK_j^T block products executed
+    pv_groups: int           # P~V row-group products executed (4 per tile when nothing is skipped)
+    valid_tiles: int         # tiles a full (causal) attention would need
+    valid_groups: int        # row-group products of those tiles that have a visible (row, key) pair
+    zero_rows: int           # rows that ended with l = 0 (must be 0 for a usable mask)
+
+    @property
+    def sparsity(self) -> float:
+        """Skipped Q_iK_j^T plus P~V products over all of them (Sec. 4.1 'Sparsity')."""
+        return 1.0 - 0.5 * (self.qk_tiles / self.valid_tiles + self.pv_groups / self.valid_groups)
+
+
+def sparse_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, mask: Optional[np.ndarray],
+                     lam: float = -np.inf, scale: Optional[float] = None, causal: bool = False,
+                     quant: bool = True, pv_dtype: str = "none") -> AttnResult:
+    """Algorithm 1's loop for one head.
+
+    quant=True: S_ij = (Q-hat_i K-hat_j^T, exact integers) * delta_Q[i] * delta_K[j] * scale with the
+    quantizers above (K smoothed).  quant=False: S_ij = scale * Q_i K_j^T in fp64.
+    pv_dtype: "fp16"/"bf16" rounds P~ to that type before the P~V product (the 16-bit matrix
+    unit's input); the row sum l always uses the unrounded P~.  mask=None means all ones.
+    """
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64)
+    N, d = Q.shape
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    Tm, Tn = nblocks(N, BQ), nblocks(N, BK)
+    if quant:
+        Qh, dQ = quantize_q(Q)
+        Kh, dK, _ = quantize_k(K)
+        Qh = Qh.astype(np.float64)
+        Kh = Kh.astype(np.float64)
+    O = np.zeros((N, d), dtype=np.float64)
+    qk_tiles = pv_groups = valid_tiles = valid_groups = zero_rows = 0
+    for i in range(Tm):
+        r0, r1 = i * BQ, min((i + 1) * BQ, N)
+        nr = r1 - r0
+        rows = np.arange(r0, r1)
+        m = np.full(nr, NEG_INF)
+        l = np.zeros(nr)
+        Oi = np.zeros((nr, d))
+        for j in range(Tn):
+            if causal and block_causal_future(i, j):
+                continue
+            valid_tiles += 1
+            c0, c1 = j * BK, min((j + 1) * BK, N)
+            for g0 in range(0, nr, ROW_GROUP):
+                last_row = r0 + min(g0 + ROW_GROUP, nr) - 1
+                if not causal or c0 <= last_row:
+                    valid_groups += 1
+            if mask is not None and mask[i, j] == 0:
+                continue
+            qk_tiles += 1
+            if quant:
+                S = (Qh[r0:r1] @ Kh[c0:c1].T) * (float(dQ[i]) * float(dK[j]) * scale)
+            else:
+                S = (Q[r0:r1] @ K[c0:c1].T) * scale
+            if causal:
+                cols = np.arange(c0, c1)
+                S = np.where(cols[None, :] > rows[:, None], NEG_INF, S)
+            m_local = S.max(axis=1)
+            m_new = np.maximum(m, m_local)
+            live = m_new > NEG_INF
+            m_safe = np.where(live, m_new, 0.0)
+            P = np.exp(S - m_safe[:, None])          # exp(-inf) = 0 for masked entries
+            with np.errstate(invalid="ignore"):
+                alpha = np.exp(m - m_new)            # nan only where both are -inf (row untouched)
+            alpha = np.where(live, alpha, 1.0)
+            l = alpha * l + P.sum(axis=1)
+            Pr = round16(P, pv_dtype)
+            for g0 in range(0, nr, ROW_GROUP):
+                g1 = min(g0 + ROW_GROUP, nr)
+                with np.errstate(invalid="ignore"):
+                    diff = np.where(m_local[g0:g1] > NEG_INF, m_local[g0:g1] - m_new[g0:g1], NEG_INF)
+                if diff.max() > lam:
+                    pv_groups += 1
+                    Oi[g0:g1] = alpha[g0:g1, None] * Oi[g0:g1] + Pr[g0:g1] @ V[c0:c1]
+                else:
+                    # a skipped group never has a changed running max, so its rescale factor is 1
+                    assert np.all(alpha[g0:g1] == 1.0)
+            m = m_new
+        dead = l == 0
+        zero_rows += int(dead.sum())
+        O[r0:r1] = np.where(dead[:, None], 0.0, Oi / np.where(dead, 1.0, l)[:, None])
+    return AttnResult(O, qk_tiles, pv_groups, valid_tiles, valid_groups, zero_rows)
+
+
+def dense_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, scale: Optional[float] = None,
+                    causal: bool = False, block_mask: Optional[np.ndarray] = None) -> np.ndarray:
+    """O = softmax(QK^T * scale) V on the full N x N score matrix (Sec. 3.1), fp64.
+
+    block_mask (Def. 2): -inf is written over every score of a block with M_g[i,j] = 0.
+    """
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64)
+    N, d = Q.shape
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    S = (Q @ K.T) * scale
+    if causal:
+        S = np.where(np.arange(N)[None, :] > np.arange(N)[:, None], NEG_INF, S)
+    if block_mask is not None:
+        full = np.repeat(np.repeat(block_mask.astype(bool), BQ, axis=0), BK, axis=1)[:N, :N]
+        S = np.where(full, S, NEG_INF)
+    mx = S.max(axis=1, keepdims=True)
+    E = np.exp(S - mx)
+    return (E / E.sum(axis=1, keepdims=True)) @ V
+
+
+def dequantized_qk(Q: np.ndarray, K: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """Q-hat*delta_Q and K-hat*delta_K as fp64 matrices (what the INT8 product effectively multiplies)."""
+    Qh, dQ = quantize_q(Q)
+    Kh, dK, _ = quantize_k(K)
+    Qd = Qh.astype(np.float64) * np.repeat(dQ.astype(np.float64), BQ)[:Qh.shape[0], None]
+    Kd = Kh.astype(np.float64) * np.repeat(dK.astype(np.float64), BK)[:Kh.shape[0], None]
+    return Qd, Kd
+
+
+def rel_l1(O: np.ndarray, O_ref: np.ndarray) -> float:
+    """Relative L1 distance sum|O - O'| / sum|O| with O the reference (Sec. 3.6)."""
+    O = np.asarray(O, dtype=np.float64)
+    O_ref = np.asarray(O_ref, dtype=np.float64)
+    return float(np.abs(O - O_ref).sum() / np.abs(O_ref).sum())
+
+
+def spargeattn(Q: np.ndarray, K: np.ndarray, V: np.ndarray, tau: float, theta: float, lam: float,
+               causal: bool = False, scale: Optional[float] = None, quant: bool = True,
+               pv_dtype: str = "none") -> Tuple[AttnResult, Prediction]:
+    """The whole of Algorithm 1 for one head: Quant, predict M_g, masked loop with the lambda skip."""
+    pred = predict(Q, K, tau, theta, scale, causal)
+    res = sparse_attention(Q, K, V, pred.mask, lam, scale, causal, quant, pv_dtype)
+    return res, pred

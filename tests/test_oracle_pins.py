@@ -1,0 +1,507 @@
+"""Pins for the CPU oracle: closed forms, invariants, brute force and library special cases.
+
+Nothing here compares the oracle with itself through the same formula: every check is either a
+value fixed by the mathematics (closed form), an independent brute-force evaluation written a
+different way, or a property the paper states (Sec. 3.1-3.4, Def. 2, Alg. 1).
+"""
+import itertools
+import math
+
+import numpy as np
+import pytest
+
+from oracle import sparge_oracle as so
+
+
+def rng(seed):
+    return np.random.default_rng(seed)
+
+
+def as16(x, dtype="fp16"):
+    if dtype == "fp16":
+        return x.astype(np.float16).astype(np.float64)
+    return so.round16(x, "bf16")
+
+
+# ------------------------------------------------------------------ pooling (Alg. 1 line 4)
+def test_pool_constant_block_and_linearity():
+    X = np.repeat(rng(0).standard_normal((3, 8)), 64, axis=0)  # 3 constant blocks of 64 rows
+    np.testing.assert_allclose(so.pool_blocks(X, 64), X[::64], rtol=0, atol=1e-14)
+    A, B = rng(1).standard_normal((200, 8)), rng(2).standard_normal((200, 8))
+    lhs = so.pool_blocks(2.0 * A - 3.0 * B, 64)
+    rhs = 2.0 * so.pool_blocks(A, 64) - 3.0 * so.pool_blocks(B, 64)
+    np.testing.assert_allclose(lhs, rhs, atol=1e-13)
+
+
+def test_pool_partial_block_uses_valid_rows_only():
+    X = np.arange(70 * 2, dtype=np.float64).reshape(70, 2)
+    p = so.pool_blocks(X, 64)
+    assert p.shape == (2, 2)
+    np.testing.assert_allclose(p[1], X[64:].sum(0) / 6.0)
+
+
+# ------------------------------------------------------------------ CosSim (Sec. 3.2)
+def test_cossim_closed_forms():
+    d, b = 16, 8
+    v = rng(3).standard_normal(d)
+    same = np.tile(v, (b, 1)) * rng(4).uniform(0.5, 2.0, (b, 1))   # same direction, any length
+    assert so.cossim_blocks(same, b)[0] == pytest.approx(1.0, abs=1e-14)
+    ortho = np.eye(d)[:b] * 3.0                                     # b orthogonal tokens -> 1/b
+    assert so.cossim_blocks(ortho, b)[0] == pytest.approx(1.0 / b, abs=1e-14)
+    anti = np.concatenate([np.tile(v, (b // 2, 1)), np.tile(-v, (b // 2, 1))])
+    assert so.cossim_blocks(anti, b)[0] == pytest.approx(0.0, abs=1e-14)
+    # two directions at angle phi, half the tokens each: mean cosine = (1 + cos phi) / 2
+    phi = 0.7
+    e1, e2 = np.eye(d)[0], math.cos(phi) * np.eye(d)[0] + math.sin(phi) * np.eye(d)[1]
+    two = np.concatenate([np.tile(e1, (b // 2, 1)), np.tile(e2, (b // 2, 1))])
+    assert so.cossim_blocks(two, b)[0] == pytest.approx((1 + math.cos(phi)) / 2, abs=1e-14)
+
+
+def test_cossim_equals_squared_norm_of_mean_unit_vector():
+    X = rng(5).standard_normal((3 * 64 + 10, 32))
+    s = so.cossim_blocks(X, 64)
+    for t in range(4):
+        blk = X[t * 64:(t + 1) * 64]
+        u = blk / np.linalg.norm(blk, axis=1, keepdims=True)
+        assert s[t] == pytest.approx(float(np.sum(u.mean(0) ** 2)), abs=1e-12)
+
+
+def test_cossim_pairwise_brute_force_and_zero_token():
+    X = rng(6).standard_normal((8, 5))
+    X[3] = 0.0
+    tot = 0.0
+    for a in range(8):
+        for b in range(8):
+            na, nb = np.linalg.norm(X[a]), np.linalg.norm(X[b])
+            tot += 0.0 if na == 0 or nb == 0 else float(X[a] @ X[b]) / (na * nb)
+    assert so.cossim_blocks(X, 8)[0] == pytest.approx(tot / 64.0, abs=1e-14)
+    # per-token rescaling leaves it unchanged
+    Y = X * rng(7).uniform(0.1, 9.0, (8, 1))
+    assert so.cossim_blocks(Y, 8)[0] == pytest.approx(tot / 64.0, abs=1e-13)
+
+
+def test_cossim_literal_formula_differs():
+    X = rng(8).standard_normal((64, 16)) + 2.0
+    G = X @ X.T
+    assert so.cossim_blocks(X, 64, literal=True)[0] == pytest.approx((G / abs(G.max())).mean())
+    assert abs(so.cossim_blocks(X, 64, literal=True)[0] - so.cossim_blocks(X, 64)[0]) > 1e-3
+
+
+# ------------------------------------------------------------------ compressed map (Alg. 1 lines 5-6)
+def test_compressed_map_rows_sum_to_one_and_uniform_for_zero_q():
+    q = np.zeros((2, 8))
+    k = rng(9).standard_normal((7, 8))
+    s_k = np.array([1, 1, 0.1, 1, 1, 0.2, 1.0])
+    P = so.compressed_map(q, k, s_k, theta=0.5, scale=0.3, causal=False)
+    np.testing.assert_allclose(P.sum(1), 1.0, atol=1e-15)
+    np.testing.assert_allclose(P[0, [0, 1, 3, 4, 6]], 0.2, atol=1e-15)
+    assert P[0, 2] == 0 and P[0, 5] == 0
+    q2 = rng(10).standard_normal((3, 8))
+    P2 = so.compressed_map(q2, k, np.ones(7), theta=0.5, scale=0.25, causal=False)
+    S = 0.25 * q2 @ k.T
+    ref = np.exp(S) / np.exp(S).sum(1, keepdims=True)     # textbook softmax
+    np.testing.assert_allclose(P2, ref, rtol=1e-13)
+
+
+def test_compressed_map_all_columns_masked_gives_zero_row():
+    P = so.compressed_map(np.ones((1, 4)), np.ones((3, 4)), np.zeros(3), 0.5, 1.0, False)
+    assert np.all(P == 0)
+
+
+def test_compressed_map_scale_matters_and_causal_future_is_zero():
+    q = rng(11).standard_normal((2, 8))
+    k = rng(12).standard_normal((4, 8))
+    P = so.compressed_map(q, k, np.ones(4), -1.0, 1.0, causal=True)
+    # Q block 0 covers rows 0..127 -> K blocks 0,1 visible, 2,3 entirely future
+    assert P[0, 2] == 0 and P[0, 3] == 0 and P[0, :2].sum() == pytest.approx(1.0)
+    assert np.all(P[1] > 0)
+
+
+# ------------------------------------------------------------------ TopCdf (Sec. 3.2)
+def test_topcdf_uniform_row_keeps_ceil_tau_n_lowest_indices():
+    for n, tau in ((10, 0.55), (7, 0.5), (33, 0.9), (16, 0.33)):
+        p = np.full(n, 1.0 / n)
+        m, _ = so.top_cdf(p, tau)
+        kkeep = math.ceil(tau * n - 1e-9)
+        assert m.sum() == kkeep and m[:kkeep].all(), (n, tau)
+
+
+def test_topcdf_minimal_prefix_with_mass_at_least_tau():
+    r = rng(13)
+    for trial in range(200):
+        n = int(r.integers(2, 40))
+        p = r.dirichlet(np.full(n, 0.3))
+        tau = float(r.uniform(0.05, 0.99))
+        m, dc = so.top_cdf(p, tau)
+        if dc.any():
+            continue
+        kept = p[m]
+        assert kept.sum() >= tau * p.sum() - 1e-15
+        assert kept.sum() - kept.min() < tau * p.sum()          # minimal: drop the smallest -> below
+        assert kept.min() >= p[~m].max() if (~m).any() else True  # it is a top-k set
+
+
+def test_topcdf_brute_force_smallest_subset():
+    r = rng(14)
+    for trial in range(30):
+        n = int(r.integers(2, 10))
+        p = r.dirichlet(np.full(n, 0.5))
+        tau = float(r.uniform(0.1, 0.95))
+        m, dc = so.top_cdf(p, tau)
+        if dc.any():
+            continue
+        best = None
+        for ksz in range(1, n + 1):
+            masses = [sum(p[list(c)]) for c in itertools.combinations(range(n), ksz)]
+            if max(masses) >= tau * p.sum():
+                best = (ksz, max(masses))
+                break
+        assert m.sum() == best[0]
+        assert p[m].sum() == pytest.approx(best[1], abs=1e-14)
+
+
+def test_topcdf_top_value_above_tau_keeps_exactly_it_and_zeros_never_kept():
+    p = np.array([0.05, 0.9, 0.05, 0.0])
+    m, _ = so.top_cdf(p, 0.5)
+    assert m.tolist() == [False, True, False, False]
+    m, _ = so.top_cdf(p, 1.0)       # tau = 1 keeps every positive entry, never a zero one
+    assert m.tolist() == [True, True, True, False]
+    m, _ = so.top_cdf(np.zeros(5), 0.9)
+    assert not m.any()
+
+
+def test_topcdf_dont_care_flags_threshold_hits():
+    p = np.array([0.5, 0.25, 0.25])
+    m, dc = so.top_cdf(p, 0.5)       # mass before rank 1 equals tau*sum exactly
+    assert dc[1] or dc[2]
+    m, dc = so.top_cdf(np.array([0.6, 0.3, 0.1]), 0.5)
+    assert not dc.any() and m.tolist() == [True, False, False]
+
+
+# ------------------------------------------------------------------ predict: overrides (Sec. 3.2 end)
+def _blocks_with_similarity(r, nblk, b, d, similar):
+    out = []
+    for t in range(nblk):
+        if similar[t]:
+            c = r.standard_normal(d)
+            out.append(c[None] + 0.05 * r.standard_normal((b, d)))
+        else:
+            out.append(r.standard_normal((b, d)))
+    return np.concatenate(out)
+
+
+def test_predict_overrides_and_pure_topcdf():
+    r = rng(15)
+    d = 32
+    Q = _blocks_with_similarity(r, 4, so.BQ, d, [True, False, True, True])
+    K = _blocks_with_similarity(r, 8, so.BK, d, [True, True, False, True, True, True, False, True])
+    pr = so.predict(Q, K, tau=0.5, theta=0.5)
+    assert pr.sim_q[1] < 0.5 < pr.sim_q[0]
+    assert pr.mask[1].all()                      # non-self-similar Q block: whole row
+    assert pr.mask[:, 2].all() and pr.mask[:, 6].all()   # non-self-similar K blocks: whole column
+    assert pr.p_hat[:, 2].max() == 0 and pr.p_hat[:, 6].max() == 0
+    assert not pr.mask.all()                     # something was filtered
+    # every selective row keeps mass >= tau among the selective columns
+    for i in (0, 2, 3):
+        assert pr.p_hat[i][pr.mask[i] == 1].sum() >= 0.5 - 1e-12
+    # theta = -inf disables the judge: the mask is TopCdf of the plain compressed map
+    pr2 = so.predict(Q, K, tau=0.5, theta=-np.inf)
+    q, k = so.pool_blocks(Q, so.BQ), so.pool_blocks(K, so.BK)
+    S = q @ k.T / math.sqrt(d)
+    P = np.exp(S - S.max(1, keepdims=True))
+    P /= P.sum(1, keepdims=True)
+    for i in range(4):
+        order = np.argsort(-P[i], kind="stable")
+        csum = np.cumsum(P[i][order])
+        nkeep = int(np.searchsorted(csum, 0.5 * P[i].sum(), side="left")) + 1
+        exp = np.zeros(8, dtype=np.uint8)
+        exp[order[:nkeep]] = 1
+        assert (pr2.mask[i] == exp).all()
+    # theta > 1: every block is a fix block -> all ones
+    assert so.predict(Q, K, tau=0.5, theta=1.5).mask.all()
+
+
+def test_predict_causal_rules():
+    r = rng(16)
+    N, d = 1024, 16
+    Q = _blocks_with_similarity(r, 8, so.BQ, d, [True] * 8)
+    K = _blocks_with_similarity(r, 16, so.BK, d, [True] * 16)
+    pr = so.predict(Q, K, tau=0.3, theta=0.2, causal=True)
+    for i in range(8):
+        assert not pr.mask[i, 2 * i + 2:].any()      # entirely-future blocks never computed
+        assert pr.mask[i, 2 * i] == 1                # block with the first row's own key is kept
+    pr_fix = so.predict(Q, K, tau=0.3, theta=1.5, causal=True)   # all fix blocks
+    for i in range(8):
+        assert pr_fix.mask[i, :2 * i + 2].all() and not pr_fix.mask[i, 2 * i + 2:].any()
+
+
+# ------------------------------------------------------------------ quantization (Alg. 1 line 3)
+def test_quant_roundtrip_within_half_step_and_amax_hits_127():
+    X = as16(rng(17).standard_normal((300, 64)) * 3.0)
+    Xq, delta = so.quantize_q(X)
+    assert Xq.dtype == np.int8 and delta.dtype == np.float32 and delta.shape == (3,)
+    for t in range(3):
+        blk = X[t * 128:(t + 1) * 128]
+        q = Xq[t * 128:(t + 1) * 128].astype(np.float64)
+        dl = float(delta[t])
+        assert np.abs(blk - q * dl).max() <= dl * (0.5 + 1e-6)
+        amax_pos = np.unravel_index(np.abs(blk).argmax(), blk.shape)
+        assert abs(q[amax_pos]) == 127
+        assert np.abs(q).max() == 127
+        assert dl == pytest.approx(np.abs(blk).max() / 127.0, rel=1e-7)
+
+
+def test_quant_matches_exact_rational_rounding_for_16bit_inputs():
+    # for 16-bit inputs 127*x is exact in fp32; the quotient rounded to nearest-even integer must
+    # equal the exactly computed rint(127*x/amax) (python fractions = independent arithmetic)
+    from fractions import Fraction
+    X = as16(rng(18).standard_normal((128, 16)))
+    Xq, _ = so.quantize_q(X)
+    amax = Fraction(float(np.abs(X).max()))
+    for (a, b), x in np.ndenumerate(X):
+        y = Fraction(127) * Fraction(float(x)) / amax
+        fl = math.floor(y)
+        rem = y - fl
+        if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and fl % 2 == 1):
+            fl += 1
+        assert int(Xq[a, b]) == fl
+
+
+def test_quant_zero_block_and_power_of_two_scaling():
+    X = as16(rng(19).standard_normal((256, 32)))
+    X[128:] = 0.0
+    Xq, delta = so.quantize_q(X)
+    assert delta[1] == 0 and not Xq[128:].any()
+    Xq2, delta2 = so.quantize_q(X * 8.0)
+    assert (Xq2 == Xq).all() and delta2[0] == delta[0] * 8.0
+
+
+def test_quant_half_to_even():
+    # amax = 127 -> y = x exactly; x = 0.5, 1.5, 2.5, -0.5, -1.5 round to 0, 2, 2, -0, -2
+    X = np.zeros((128, 8))
+    X[0, 0] = 127.0
+    X[1, :5] = [0.5, 1.5, 2.5, -0.5, -1.5]
+    Xq, delta = so.quantize_q(X)
+    assert delta[0] == 1.0
+    assert Xq[1, :5].tolist() == [0, 2, 2, 0, -2]
+
+
+def test_k_smoothing_mean_and_shift_invariance():
+    r = rng(20)
+    K = as16(r.standard_normal((320, 16)) + 1.5, "bf16")
+    Kq, dK, mean = so.quantize_k(K)
+    assert mean.dtype == np.float32
+    np.testing.assert_allclose(mean, K.mean(0), rtol=1e-6)
+    assert abs(float((Kq.astype(np.float64) * np.repeat(dK, 64)[:, None]).mean())) < 0.05
+    # softmax attention does not change when a constant vector is removed from every key
+    Q, V = r.standard_normal((320, 16)), r.standard_normal((320, 16))
+    np.testing.assert_allclose(so.dense_attention(Q, K, V), so.dense_attention(Q, K - K.mean(0), V),
+                               atol=1e-12)
+    # nor does the compressed map P-hat
+    q, k1, k2 = so.pool_blocks(Q, 128), so.pool_blocks(K, 64), so.pool_blocks(K - K.mean(0), 64)
+    ones = np.ones(5)
+    np.testing.assert_allclose(so.compressed_map(q, k1, ones, 0.0, 0.25, False),
+                               so.compressed_map(q, k2, ones, 0.0, 0.25, False), atol=1e-13)
+
+
+def test_k_mean_is_exact_sum_over_n():
+    from fractions import Fraction
+    K = as16(rng(21).standard_normal((130, 3)) * 100.0, "bf16")
+    mean = so.k_mean(K)
+    for c in range(3):
+        exact = sum(Fraction(float(v)) for v in K[:, c]) / 130
+        assert float(mean[c]) == float(np.float32(float(exact)))
+
+
+# ------------------------------------------------------------------ dense reference vs textbook
+def test_dense_attention_textbook_and_rows_of_p_sum_to_one():
+    r = rng(22)
+    Q, K, V = r.standard_normal((70, 8)), r.standard_normal((70, 8)), r.standard_normal((70, 8))
+    O = so.dense_attention(Q, K, V)
+    ref = np.zeros_like(O)
+    for a in range(70):      # scalar loops: independent of the matrix code
+        w = [math.exp(sum(Q[a, c] * K[b, c] for c in range(8)) / math.sqrt(8)) for b in range(70)]
+        z = sum(w)
+        for c in range(8):
+            ref[a, c] = sum(w[b] * V[b, c] for b in range(70)) / z
+    np.testing.assert_allclose(O, ref, atol=1e-12)
+    # V = ones -> every output is exactly the row sum of P = 1
+    np.testing.assert_allclose(so.dense_attention(Q, K, np.ones((70, 8))), 1.0, atol=1e-14)
+    Oc = so.dense_attention(Q, K, V, causal=True)
+    np.testing.assert_allclose(Oc[0], V[0], atol=1e-14)      # first row sees only itself
+
+
+def test_dense_attention_permutation_invariance():
+    r = rng(23)
+    Q, K, V = (r.standard_normal((50, 8)) for _ in range(3))
+    p, pq = r.permutation(50), r.permutation(50)
+    O = so.dense_attention(Q, K, V)
+    np.testing.assert_allclose(so.dense_attention(Q[pq], K[p], V[p]), O[pq], atol=1e-13)
+
+
+# ------------------------------------------------------------------ flash loop (Sec. 3.1, Def. 2)
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("N", [256, 300, 77])
+def test_loop_all_ones_no_skip_no_quant_equals_dense(N, causal):
+    r = rng(24 + N)
+    Q, K, V = (r.standard_normal((N, 16)) for _ in range(3))
+    res = so.sparse_attention(Q, K, V, None, lam=-np.inf, causal=causal, quant=False)
+    np.testing.assert_allclose(res.O, so.dense_attention(Q, K, V, causal=causal), atol=1e-12)
+    assert res.zero_rows == 0 and res.sparsity == pytest.approx(0.0)
+    # independent count: a (row group, K block) pair is needed iff some key of the block is visible
+    need = 0
+    for g in range(math.ceil(N / 32)):
+        last_row = min(32 * g + 31, N - 1)
+        for j in range(so.nblocks(N, 64)):
+            need += (not causal) or (64 * j <= last_row)
+    assert res.pv_groups == need == res.valid_groups
+
+
+def test_whole_operator_dense_switches_equal_brute_force():
+    # tau=1, theta>1 (all fix blocks), lambda=-inf, quantization off -> plain softmax attention
+    r = rng(30)
+    Q, K, V = (r.standard_normal((200, 16)) for _ in range(3))
+    res, pred = so.spargeattn(Q, K, V, tau=1.0, theta=1.5, lam=-np.inf, quant=False)
+    assert pred.mask.all()
+    np.testing.assert_allclose(res.O, so.dense_attention(Q, K, V), atol=1e-12)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_loop_with_block_mask_equals_dense_with_minus_inf_blocks(causal):
+    r = rng(31)
+    N = 520
+    Q, K, V = (r.standard_normal((N, 16)) for _ in range(3))
+    Tm, Tn = so.nblocks(N, 128), so.nblocks(N, 64)
+    mask = (r.uniform(size=(Tm, Tn)) < 0.5).astype(np.uint8)
+    for i in range(Tm):
+        mask[i, 2 * i] = 1           # keep every row alive (also under causal)
+    res = so.sparse_attention(Q, K, V, mask, lam=-np.inf, causal=causal, quant=False)
+    ref = so.dense_attention(Q, K, V, causal=causal, block_mask=mask)
+    np.testing.assert_allclose(res.O, ref, atol=1e-12)
+    assert res.zero_rows == 0
+
+
+def test_loop_quantized_equals_dense_on_dequantized_operands():
+    r = rng(32)
+    N = 330
+    Q, K, V = as16(r.standard_normal((N, 32))), as16(r.standard_normal((N, 32)) + 0.7), r.standard_normal((N, 32))
+    res = so.sparse_attention(Q, K, V, None, lam=-np.inf, quant=True)
+    Qd, Kd = so.dequantized_qk(Q, K)
+    np.testing.assert_allclose(res.O, so.dense_attention(Qd, Kd, V), atol=1e-11)
+    # and INT8 quantization stays close to the exact result
+    assert so.rel_l1(res.O, so.dense_attention(Q, K, V)) < 3e-2
+
+
+def test_fully_masked_row_reports_zero_rows():
+    r = rng(33)
+    Q, K, V = (r.standard_normal((256, 8)) for _ in range(3))
+    mask = np.ones((2, 4), dtype=np.uint8)
+    mask[1] = 0
+    res = so.sparse_attention(Q, K, V, mask, quant=False)
+    assert res.zero_rows == 128 and np.all(res.O[128:] == 0)
+
+
+# ------------------------------------------------------------------ lambda skip (Sec. 3.4)
+def _peaky_inputs(seed, N=512, d=16):
+    r = rng(seed)
+    cent = r.standard_normal((N // 64, d)) * 2.5
+    K = np.repeat(cent, 64, axis=0) + 0.2 * r.standard_normal((N, d))
+    Q = np.repeat(cent, 64, axis=0) * 1.5 + 0.2 * r.standard_normal((N, d))
+    V = r.standard_normal((N, d))
+    return Q, K, V
+
+
+def test_lambda_minus_inf_is_mask_only_and_skips_grow_with_lambda():
+    Q, K, V = _peaky_inputs(40)
+    base = so.sparse_attention(Q, K, V, None, lam=-np.inf, quant=False)
+    prev = base.pv_groups
+    seen_skip = False
+    for lam in (-60.0, -30.0, -15.0, -8.0, -4.0, -2.0):
+        res = so.sparse_attention(Q, K, V, None, lam=lam, quant=False)
+        assert res.pv_groups <= prev
+        assert res.qk_tiles == base.qk_tiles
+        prev = res.pv_groups
+        seen_skip |= res.pv_groups < base.pv_groups
+    assert seen_skip
+
+
+def test_lambda_error_bound_per_row():
+    Q, K, V = _peaky_inputs(41)
+    N = Q.shape[0]
+    base = so.sparse_attention(Q, K, V, None, lam=-np.inf, quant=False)
+    for lam in (-12.0, -6.0, -3.0):
+        res = so.sparse_attention(Q, K, V, None, lam=lam, quant=False)
+        skipped_groups = base.pv_groups - res.pv_groups
+        assert skipped_groups > 0
+        # every dropped term is <= e^lam * |V| relative to the running max at that time, which is
+        # <= the final max; l >= 1 in units of the final max; at most N columns are dropped
+        bound = N * math.exp(lam) * np.abs(V).max()
+        assert np.abs(res.O - base.O).max() <= bound
+    # a looser analytic check with fewer dropped columns: error shrinks as lambda decreases
+    e3 = np.abs(so.sparse_attention(Q, K, V, None, lam=-3.0, quant=False).O - base.O).max()
+    e12 = np.abs(so.sparse_attention(Q, K, V, None, lam=-12.0, quant=False).O - base.O).max()
+    assert e12 < e3
+
+
+def test_lambda_threshold_is_strict_and_per_row_group():
+    # one Q block (128 rows), two K blocks; all scores in block 0 are 0, block 1 scores are -g per
+    # row group g: row group w has m_local - m = -(w+1)*2 in block 1 -> executed iff -(w+1)*2 > lam
+    d = 4
+    Q = np.zeros((128, d))
+    for w in range(4):
+        Q[32 * w:32 * (w + 1), 0] = (w + 1) * 2.0
+    K = np.zeros((128, d))
+    K[64:, 0] = -1.0
+    V = rng(42).standard_normal((128, d))
+    for lam, expect in ((-1.0, 4 + 0), (-2.0, 4 + 0), (-2.5, 4 + 1), (-4.0, 4 + 1), (-4.5, 4 + 2), (-100.0, 8)):
+        res = so.sparse_attention(Q, K, V, None, lam=lam, scale=1.0, quant=False)
+        assert res.pv_groups == expect, (lam, res.pv_groups)
+    # l is updated even for skipped groups: output = sum over block 0 of V / (64 + 64 e^{-2(w+1)})
+    res = so.sparse_attention(Q, K, V, None, lam=-1.0, scale=1.0, quant=False)
+    for w in range(4):
+        expect = V[:64].sum(0) / (64.0 + 64.0 * math.exp(-2.0 * (w + 1)))
+        np.testing.assert_allclose(res.O[32 * w], expect, atol=1e-13)
+
+
+def test_sparsity_accounting():
+    Q, K, V = (rng(43).standard_normal((256, 8)) for _ in range(3))
+    mask = np.array([[1, 0, 0, 0], [1, 1, 0, 0]], dtype=np.uint8)
+    res = so.sparse_attention(Q, K, V, mask, quant=False)
+    assert (res.qk_tiles, res.pv_groups, res.valid_tiles, res.valid_groups) == (3, 12, 8, 32)
+    assert res.sparsity == pytest.approx(1 - (3 + 3) / 16)
+    resc = so.sparse_attention(Q, K, V, None, causal=True, quant=False)
+    assert resc.valid_tiles == 2 + 4 and resc.sparsity == pytest.approx(0.0)
+
+
+def test_pv_rounding_only_touches_numerator():
+    Q, K, V = _peaky_inputs(44, N=256)
+    a = so.sparse_attention(Q, K, V, None, quant=False, pv_dtype="none")
+    b = so.sparse_attention(Q, K, np.ones_like(V), None, quant=False, pv_dtype="bf16")
+    # with V = 1 the output is rowsum(round(P~))/rowsum(P~): close to, but not exactly, 1
+    assert np.abs(b.O - 1.0).max() < 2 ** -8 and np.abs(b.O - 1.0).max() > 0
+    assert so.rel_l1(so.sparse_attention(Q, K, V, None, quant=False, pv_dtype="fp16").O, a.O) < 1e-3
+
+
+def test_round16_ties_and_exactness():
+    assert so.round16(np.array([1.0 + 2 ** -8]), "bf16")[0] == 1.0            # tie -> even
+    assert so.round16(np.array([1.0 + 3 * 2 ** -8]), "bf16")[0] == 1.0 + 2 ** -6
+    assert so.round16(np.array([0.333251953125]), "fp16")[0] == 0.333251953125  # exact fp16 value
+    assert so.rel_l1(np.array([1.0, -3.0]), np.array([2.0, -2.0])) == pytest.approx(0.5)
+
+
+def test_judge_matters_on_non_self_similar_blocks():
+    # synthetic analogue of the self-similarity-judge ablation (App. A.2): keys of block 5 are not
+    # self-similar but a few of them matter a lot; without the judge (theta=-inf) the compressed
+    # token hides them and the error grows
+    r = rng(45)
+    N, d = 1024, 32
+    cent = r.standard_normal((N // 64, d))
+    K = np.repeat(cent, 64, axis=0) + 0.1 * r.standard_normal((N, d))
+    Q = r.standard_normal((N // 128, d)).repeat(128, axis=0) + 0.1 * r.standard_normal((N, d))
+    K[5 * 64:6 * 64] = r.standard_normal((64, d)) * 0.3
+    K[5 * 64:5 * 64 + 4] = Q[::128][:4] * 3.0       # needles inside the noisy block
+    V = r.standard_normal((N, d))
+    ref = so.dense_attention(Q, K, V)
+    with_j, _ = so.spargeattn(Q, K, V, tau=0.6, theta=0.5, lam=-np.inf, quant=False)
+    no_j, _ = so.spargeattn(Q, K, V, tau=0.6, theta=-np.inf, lam=-np.inf, quant=False)
+    assert so.rel_l1(with_j.O, ref) < so.rel_l1(no_j.O, ref)
