@@ -1,0 +1,129 @@
+/*
+ * sparge.h -- C ABI of the MI355X (gfx950) implementation of SpargeAttn's hot path:
+ * block-sparse, INT8-quantized attention O = softmax(QK^T/sqrt(d))V driven by a two-stage
+ * online filter (arXiv 2502.18137, Algorithm 1).
+ *
+ * General rules for every entry point
+ *   - Every data pointer is DEVICE memory owned by the caller unless marked "host".  The library
+ *     never allocates, never frees, keeps no pointer after returning and holds no global state
+ *     besides a thread-local error string.
+ *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = default
+ *     stream).  No entry point synchronises the host; results are valid after the stream reaches
+ *     the end of the enqueued work.
+ *   - Return value: SPARGE_OK or a negative error code; sparge_last_error() then describes it.
+ *     Invalid arguments are rejected before anything is enqueued.
+ *   - Tensors Q, K, V, O share one descriptor: logical shape [B, H, N, d], element strides
+ *     stride_b / stride_h / stride_n, d contiguous (stride 1).  [B,H,N,d] and [B,N,H,d] both fit.
+ *     Rows must be 16-byte aligned (base pointers 16-byte aligned, strides multiples of 8 elements).
+ *   - Block geometry is fixed (Alg. 1 line 2; App. A.1): b_q = 128 query rows, b_k = 64 key rows,
+ *     row groups of 32 query rows (b_q / c_w, c_w = 4) for the stage-2 test.
+ *     T_m = ceil(N/128), T_n = ceil(N/64).  A partial last block uses its valid rows only.
+ *   - Supported: d in {64, 128}; dtype fp16 or bf16; H <= SPARGE_MAX_HEADS; T_n <= SPARGE_MAX_TN.
+ *   - Hyper-parameters (Sec. 3.6) are per head, host arrays of length H: tau in (0,1],
+ *     theta any real (theta > 1 makes every block a fix block; theta = -inf disables the judge),
+ *     lambda < 0 (-INFINITY = never skip).
+ *   - sm_scale <= 0 selects 1/sqrt(d).
+ */
+#ifndef SPARGE_H
+#define SPARGE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { SPARGE_OK = 0, SPARGE_EINVAL = -1, SPARGE_EUNSUPPORTED = -2, SPARGE_ENOSPACE = -3, SPARGE_EHIP = -4 };
+enum { SPARGE_F16 = 0, SPARGE_BF16 = 1 };
+enum { SPARGE_BQ = 128, SPARGE_BK = 64, SPARGE_ROW_GROUP = 32 };
+enum { SPARGE_MAX_HEADS = 128, SPARGE_MAX_TN = 4096 };
+
+/* which entry point a workspace is sized for */
+enum { SPARGE_WS_QUANTIZE = 0, SPARGE_WS_PREDICT = 1, SPARGE_WS_ATTN = 2, SPARGE_WS_ATTN_QUANTIZED = 3,
+       SPARGE_WS_FORWARD = 4 };
+
+typedef struct sparge_desc {
+    int32_t B, H, N, d;
+    int32_t dtype;                          /* SPARGE_F16 | SPARGE_BF16 */
+    int64_t stride_b, stride_h, stride_n;   /* in elements; the d axis is contiguous */
+} sparge_desc;
+
+/* Description of the last error on the calling thread (host string, never NULL). */
+const char* sparge_last_error(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int sparge_version(void);
+
+/* Bytes of device scratch `ws` the given entry point (SPARGE_WS_*) needs for this shape.
+ * The workspace needs 256-byte alignment and carries no state between calls. */
+int sparge_workspace_bytes(const sparge_desc* desc, int entry, size_t* bytes /* host, out */);
+
+/*
+ * Quant (Alg. 1 line 3; Sec. 3.5): per-block symmetric INT8 quantization of Q (128-row blocks)
+ * and of K minus its per-(batch,head) token mean (64-row blocks).
+ *   amax = max|x| over the block; scale = amax/127; x_hat = rint_half_even(x * (127/amax)), all fp32;
+ *   a zero block gives x_hat = 0, scale = 0.  k_mean = fp32(sum_t K[t,:] (fp64) / N).
+ * Outputs: Qq, Kq int8 [B,H,N,d] contiguous; q_scale fp32 [B,H,T_m]; k_scale fp32 [B,H,T_n];
+ *          k_mean fp32 [B,H,d].
+ */
+int sparge_quantize(const void* Q, const void* K, const sparge_desc* desc,
+                    int8_t* Qq, int8_t* Kq, float* q_scale, float* k_scale, float* k_mean,
+                    void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * Stage-1 predictor (Alg. 1 lines 4-6; Sec. 3.2): block means q_i, k_j; block self-similarity
+ * s = mean pairwise cosine of a block's tokens; S_hat = sm_scale * q k^T with column j set to -inf
+ * when s_kj < theta (and, if causal, when block j lies entirely after block i);
+ * P_hat = row softmax; M[i,:] = TopCdf(P_hat[i], tau) (smallest descending prefix whose mass
+ * reaches tau * sum; ties by ascending j; zero-probability entries never selected); then
+ * M[i,:] = 1 if s_qi < theta, M[:,j] = 1 if s_kj < theta; if causal, entirely-future blocks are 0
+ * and the block holding the first diagonal key of Q block i (j = 2i) is 1.
+ * Outputs: mask uint8 [B,H,T_m,T_n] (1 = compute); optional sim_q fp64 [B,H,T_m] and
+ *          sim_k fp64 [B,H,T_n] (NULL to skip).
+ * tau, theta: host float arrays [H].
+ */
+int sparge_predict(const void* Q, const void* K, const sparge_desc* desc,
+                   const float* tau, const float* theta, float sm_scale, int causal,
+                   uint8_t* mask, double* sim_q, double* sim_k,
+                   void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * Sparse flash loop with the stage-2 filter (Alg. 1 lines 7-20; Sec. 3.1, 3.3, 3.4) on
+ * pre-quantized Q/K (outputs of sparge_quantize; k_mean is not needed: softmax is invariant to it).
+ * For every Q block i and every kept K block j (mask[i,j] != 0, ascending j):
+ *   S = (Qq_i Kq_j^T in int32) * q_scale[i] * k_scale[j] * sm_scale (+ element-wise causal -inf),
+ *   m_local = rowmax(S), m_ij = max(m_i,j-1, m_local), P~ = exp(S - m_ij),
+ *   l_ij = exp(m_i,j-1 - m_ij) l_i,j-1 + rowsum(P~)            -- always;
+ *   for each 32-row group: if max(m_local - m_ij) > lambda:
+ *       O_ij = diag(exp(m_i,j-1 - m_ij)) O_i,j-1 + P~(rounded to V's dtype) V_j   -- else skipped;
+ * finally O_i = diag(l)^-1 O_i.  Rows without any kept visible key get 0.
+ * mask: uint8 [B,H,T_m,T_n] or NULL (= all ones).  lambda: host float [H].
+ * O: same dtype/strides as V (desc).  stats: optional uint64 [B,H,4] = {QK^T tiles executed,
+ * P~V row-group products executed, tiles a full attention needs, row-group products a full
+ * attention needs}; it is overwritten, not accumulated.
+ */
+int sparge_attn_quantized(const int8_t* Qq, const int8_t* Kq, const float* q_scale, const float* k_scale,
+                          const void* V, const sparge_desc* desc, const uint8_t* mask,
+                          const float* lambda, float sm_scale, int causal,
+                          void* O, uint64_t* stats, void* ws, size_t ws_bytes, void* hip_stream);
+
+/* Same as sparge_quantize followed by sparge_attn_quantized, with Q-hat/K-hat kept in `ws`. */
+int sparge_attn(const void* Q, const void* K, const void* V, const sparge_desc* desc,
+                const uint8_t* mask, const float* lambda, float sm_scale, int causal,
+                void* O, uint64_t* stats, void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * All of Algorithm 1: Quant, predict M_g, masked loop with the lambda skip.  Q and K are each read
+ * once for block statistics + Q quantization and K is read a second time for its quantization.
+ * mask_out: optional uint8 [B,H,T_m,T_n] receiving M_g (NULL: kept in `ws` only).
+ */
+int sparge_forward(const void* Q, const void* K, const void* V, const sparge_desc* desc,
+                   const float* tau, const float* theta, const float* lambda,
+                   float sm_scale, int causal, void* O, uint8_t* mask_out, uint64_t* stats,
+                   void* ws, size_t ws_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPARGE_H */

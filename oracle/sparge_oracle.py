@@ -23,7 +23,8 @@ Readings of the paper where it is silent or ambiguous (each also listed in the d
   * lambda test (Alg. 1 line 15): execute iff max over the row group's valid rows of
     (m_local - m_ij) > lambda; l is always updated (line 13 precedes line 15).
   * Quant (Alg. 1 line 3, SageAttention per-block INT8): symmetric, scale = amax/127, round half to
-    even, K smoothed by its per-head token mean.  The fp32 operation sequence is spelled out in
+    even, K smoothed by its per-head token mean.  The fp32 operation sequence (one reciprocal per
+    block, one multiplication per element) is spelled out in
     quantize_q / quantize_k and is part of the specification.
 """
 from __future__ import annotations
@@ -199,8 +200,8 @@ def predict(Q: np.ndarray, K: np.ndarray, tau: float, theta: float, scale: Optio
 # ----------------------------------------------------------------------------------------------
 def _quant_blocks(X32: np.ndarray, b: int) -> Tuple[np.ndarray, np.ndarray]:
     """Per-block INT8 quantization of an fp32 matrix, fp32 arithmetic with these rounding points:
-    amax = max|x| over the block's valid rows; delta = fl32(amax/127);
-    x_hat = rint_half_even(fl32(fl32(127*x)/amax)); a zero block gives x_hat = 0, delta = 0."""
+    amax = max|x| over the block's valid rows; delta = fl32(amax/127); r = fl32(127/amax);
+    x_hat = rint_half_even(fl32(x*r)); a zero block gives x_hat = 0, delta = 0."""
     assert X32.dtype == np.float32
     N = X32.shape[0]
     T = nblocks(N, b)
@@ -213,8 +214,9 @@ def _quant_blocks(X32: np.ndarray, b: int) -> Tuple[np.ndarray, np.ndarray]:
         if amax == 0:
             continue
         delta[t] = amax / c127
-        y = (c127 * blk) / amax  # two correctly rounded fp32 operations
-        assert y.dtype == np.float32
+        r = c127 / amax
+        y = blk * r  # one correctly rounded fp32 multiplication per element
+        assert y.dtype == np.float32 and np.abs(y).max() <= 127.5
         Xq[t * b:(t + 1) * b] = np.rint(y).astype(np.int8)  # rint: ties to even
     return Xq, delta
 

@@ -1,0 +1,18 @@
+"""MI355X-native SpargeAttn hot path: thin Python binding over the C-ABI library libsparge.so.
+
+Importing the package does not load the library; the first call does, and fails loudly if the
+library has not been built (python -m paper_2502_18137_amd.build).
+"""
+from .binding import (  # noqa: F401
+    SpargeError,
+    library_path,
+    load_library,
+    sparge_attn,
+    sparge_attn_quantized,
+    sparge_forward,
+    sparge_predict,
+    sparge_quantize,
+    sparge_version,
+    sparge_workspace_bytes,
+    WS_ATTN, WS_ATTN_QUANTIZED, WS_FORWARD, WS_PREDICT, WS_QUANTIZE,
+)

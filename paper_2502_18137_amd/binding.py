@@ -1,0 +1,232 @@
+"""ctypes binding for libsparge.so: argument marshalling only.
+
+Every function mirrors the C entry point of the same name (include/sparge.h).  Tensors are torch
+tensors on the GPU; outputs and the workspace are allocated here with torch (device memory and
+streams are all torch is used for) and every step of the path runs inside the library's kernels.
+There is no fallback: if the library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence, Tuple, Union
+
+import torch
+
+WS_QUANTIZE, WS_PREDICT, WS_ATTN, WS_ATTN_QUANTIZED, WS_FORWARD = range(5)
+BQ, BK = 128, 64
+
+_LIB: Optional[ctypes.CDLL] = None
+
+
+class SpargeError(RuntimeError):
+    pass
+
+
+class _Desc(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int32), ("d", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64),
+                ("stride_n", ctypes.c_int64)]
+
+
+def library_path() -> str:
+    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsparge.so")
+
+
+def load_library() -> ctypes.CDLL:
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not os.path.exists(path):
+        raise SpargeError(f"{path} is missing: build it with `python -m paper_2502_18137_amd.build` "
+                          "(there is no fallback path)")
+    lib = ctypes.CDLL(path)
+    vp, f32p = ctypes.c_void_p, ctypes.POINTER(ctypes.c_float)
+    dp = ctypes.POINTER(_Desc)
+    lib.sparge_last_error.restype = ctypes.c_char_p
+    lib.sparge_last_error.argtypes = []
+    lib.sparge_version.restype = ctypes.c_int
+    lib.sparge_workspace_bytes.argtypes = [dp, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t)]
+    lib.sparge_quantize.argtypes = [vp, vp, dp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.sparge_predict.argtypes = [vp, vp, dp, f32p, f32p, ctypes.c_float, ctypes.c_int, vp, vp, vp, vp,
+                                   ctypes.c_size_t, vp]
+    lib.sparge_attn_quantized.argtypes = [vp, vp, vp, vp, vp, dp, vp, f32p, ctypes.c_float, ctypes.c_int, vp, vp,
+                                          vp, ctypes.c_size_t, vp]
+    lib.sparge_attn.argtypes = [vp, vp, vp, dp, vp, f32p, ctypes.c_float, ctypes.c_int, vp, vp, vp,
+                                ctypes.c_size_t, vp]
+    lib.sparge_forward.argtypes = [vp, vp, vp, dp, f32p, f32p, f32p, ctypes.c_float, ctypes.c_int, vp, vp, vp, vp,
+                                   ctypes.c_size_t, vp]
+    for name in ("sparge_workspace_bytes", "sparge_quantize", "sparge_predict", "sparge_attn_quantized",
+                 "sparge_attn", "sparge_forward"):
+        getattr(lib, name).restype = ctypes.c_int
+    _LIB = lib
+    return lib
+
+
+def _check(rc: int) -> None:
+    if rc != 0:
+        raise SpargeError(f"libsparge error {rc}: {load_library().sparge_last_error().decode()}")
+
+
+def _desc(x: torch.Tensor) -> _Desc:
+    if x.dim() != 4:
+        raise SpargeError("expected a [B, H, N, d] tensor")
+    if not x.is_cuda:
+        raise SpargeError("tensors must live on the GPU")
+    if x.stride(3) != 1:
+        raise SpargeError("the head dimension must be contiguous")
+    if x.dtype == torch.float16:
+        dt = 0
+    elif x.dtype == torch.bfloat16:
+        dt = 1
+    else:
+        raise SpargeError(f"dtype {x.dtype} not supported (fp16 or bf16)")
+    B, H, N, d = x.shape
+    return _Desc(B, H, N, d, dt, x.stride(0), x.stride(1), x.stride(2))
+
+
+def _same_layout(ref: torch.Tensor, *others: torch.Tensor) -> None:
+    for o in others:
+        if o.shape != ref.shape or o.stride() != ref.stride() or o.dtype != ref.dtype or o.device != ref.device:
+            raise SpargeError("Q, K, V (and O) must share shape, strides, dtype and device")
+
+
+def _per_head(v: Union[float, Sequence[float]], H: int):
+    vals = [float(v)] * H if isinstance(v, (int, float)) else [float(x) for x in v]
+    if len(vals) != H:
+        raise SpargeError(f"expected {H} per-head values, got {len(vals)}")
+    return (ctypes.c_float * H)(*vals)
+
+
+def _stream() -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> ctypes.c_void_p:
+    return ctypes.c_void_p(0 if t is None else t.data_ptr())
+
+
+def sparge_version() -> int:
+    return load_library().sparge_version()
+
+
+def sparge_workspace_bytes(x: torch.Tensor, entry: int) -> int:
+    n = ctypes.c_size_t(0)
+    d = _desc(x)
+    _check(load_library().sparge_workspace_bytes(ctypes.byref(d), entry, ctypes.byref(n)))
+    return int(n.value)
+
+
+def _workspace(x: torch.Tensor, entry: int, ws: Optional[torch.Tensor]) -> torch.Tensor:
+    need = sparge_workspace_bytes(x, entry)
+    if ws is None:
+        ws = torch.empty(need, dtype=torch.uint8, device=x.device)
+    return ws
+
+
+def _blocks(N: int) -> Tuple[int, int]:
+    return (N + BQ - 1) // BQ, (N + BK - 1) // BK
+
+
+def sparge_quantize(Q: torch.Tensor, K: torch.Tensor, ws: Optional[torch.Tensor] = None):
+    """-> (Qq int8 [B,H,N,d], Kq int8, q_scale fp32 [B,H,Tm], k_scale fp32 [B,H,Tn], k_mean fp32 [B,H,d])."""
+    _same_layout(Q, K)
+    d = _desc(Q)
+    B, H, N, dim = Q.shape
+    Tm, Tn = _blocks(N)
+    dev = Q.device
+    Qq = torch.empty((B, H, N, dim), dtype=torch.int8, device=dev)
+    Kq = torch.empty((B, H, N, dim), dtype=torch.int8, device=dev)
+    qs = torch.empty((B, H, Tm), dtype=torch.float32, device=dev)
+    ks = torch.empty((B, H, Tn), dtype=torch.float32, device=dev)
+    km = torch.empty((B, H, dim), dtype=torch.float32, device=dev)
+    ws = _workspace(Q, WS_QUANTIZE, ws)
+    _check(load_library().sparge_quantize(_ptr(Q), _ptr(K), ctypes.byref(d), _ptr(Qq), _ptr(Kq), _ptr(qs), _ptr(ks),
+                                          _ptr(km), _ptr(ws), ws.numel(), _stream()))
+    return Qq, Kq, qs, ks, km
+
+
+def sparge_predict(Q: torch.Tensor, K: torch.Tensor, tau, theta, causal: bool = False, sm_scale: float = 0.0,
+                   return_sims: bool = False, ws: Optional[torch.Tensor] = None):
+    """-> mask uint8 [B,H,Tm,Tn] (and sim_q, sim_k fp64 if return_sims)."""
+    _same_layout(Q, K)
+    d = _desc(Q)
+    B, H, N, _ = Q.shape
+    Tm, Tn = _blocks(N)
+    mask = torch.empty((B, H, Tm, Tn), dtype=torch.uint8, device=Q.device)
+    sq = torch.empty((B, H, Tm), dtype=torch.float64, device=Q.device) if return_sims else None
+    sk = torch.empty((B, H, Tn), dtype=torch.float64, device=Q.device) if return_sims else None
+    ws = _workspace(Q, WS_PREDICT, ws)
+    _check(load_library().sparge_predict(_ptr(Q), _ptr(K), ctypes.byref(d), _per_head(tau, H), _per_head(theta, H),
+                                         float(sm_scale), int(causal), _ptr(mask), _ptr(sq), _ptr(sk), _ptr(ws),
+                                         ws.numel(), _stream()))
+    return (mask, sq, sk) if return_sims else mask
+
+
+def sparge_attn_quantized(Qq, Kq, q_scale, k_scale, V: torch.Tensor, mask: Optional[torch.Tensor], lam,
+                          causal: bool = False, sm_scale: float = 0.0, return_stats: bool = False,
+                          ws: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None):
+    """-> O (same layout as V) (and stats uint64-as-int64 [B,H,4] if return_stats)."""
+    d = _desc(V)
+    B, H, N, dim = V.shape
+    Tm, Tn = _blocks(N)
+    for t, shape, dt in ((Qq, (B, H, N, dim), torch.int8), (Kq, (B, H, N, dim), torch.int8),
+                         (q_scale, (B, H, Tm), torch.float32), (k_scale, (B, H, Tn), torch.float32)):
+        if tuple(t.shape) != shape or t.dtype != dt or not t.is_contiguous() or t.device != V.device:
+            raise SpargeError("quantized operands must be contiguous outputs of sparge_quantize for this shape")
+    if mask is not None and (tuple(mask.shape) != (B, H, Tm, Tn) or mask.dtype != torch.uint8
+                             or not mask.is_contiguous() or mask.device != V.device):
+        raise SpargeError("mask must be a contiguous uint8 [B,H,Tm,Tn] tensor")
+    O = torch.empty_like(V) if out is None else out
+    _same_layout(V, O)
+    stats = torch.zeros((B, H, 4), dtype=torch.int64, device=V.device) if return_stats else None
+    ws = _workspace(V, WS_ATTN_QUANTIZED, ws)
+    _check(load_library().sparge_attn_quantized(_ptr(Qq), _ptr(Kq), _ptr(q_scale), _ptr(k_scale), _ptr(V),
+                                                ctypes.byref(d), _ptr(mask), _per_head(lam, H), float(sm_scale),
+                                                int(causal), _ptr(O), _ptr(stats), _ptr(ws), ws.numel(), _stream()))
+    return (O, stats) if return_stats else O
+
+
+def sparge_attn(Q, K, V, mask: Optional[torch.Tensor], lam, causal: bool = False, sm_scale: float = 0.0,
+                return_stats: bool = False, ws: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None):
+    """Quantize + sparse attention.  -> O (and stats)."""
+    _same_layout(Q, K, V)
+    d = _desc(Q)
+    B, H, N, _ = Q.shape
+    Tm, Tn = _blocks(N)
+    if mask is not None and (tuple(mask.shape) != (B, H, Tm, Tn) or mask.dtype != torch.uint8
+                             or not mask.is_contiguous() or mask.device != Q.device):
+        raise SpargeError("mask must be a contiguous uint8 [B,H,Tm,Tn] tensor")
+    O = torch.empty_like(V) if out is None else out
+    _same_layout(V, O)
+    stats = torch.zeros((B, H, 4), dtype=torch.int64, device=Q.device) if return_stats else None
+    ws = _workspace(Q, WS_ATTN, ws)
+    _check(load_library().sparge_attn(_ptr(Q), _ptr(K), _ptr(V), ctypes.byref(d), _ptr(mask), _per_head(lam, H),
+                                      float(sm_scale), int(causal), _ptr(O), _ptr(stats), _ptr(ws), ws.numel(),
+                                      _stream()))
+    return (O, stats) if return_stats else O
+
+
+def sparge_forward(Q, K, V, tau, theta, lam, causal: bool = False, sm_scale: float = 0.0,
+                   return_mask: bool = False, return_stats: bool = False, ws: Optional[torch.Tensor] = None,
+                   out: Optional[torch.Tensor] = None):
+    """All of Algorithm 1.  -> O (and mask, stats when requested, in that order)."""
+    _same_layout(Q, K, V)
+    d = _desc(Q)
+    B, H, N, _ = Q.shape
+    Tm, Tn = _blocks(N)
+    O = torch.empty_like(V) if out is None else out
+    _same_layout(V, O)
+    mask = torch.empty((B, H, Tm, Tn), dtype=torch.uint8, device=Q.device) if return_mask else None
+    stats = torch.zeros((B, H, 4), dtype=torch.int64, device=Q.device) if return_stats else None
+    ws = _workspace(Q, WS_FORWARD, ws)
+    _check(load_library().sparge_forward(_ptr(Q), _ptr(K), _ptr(V), ctypes.byref(d), _per_head(tau, H),
+                                         _per_head(theta, H), _per_head(lam, H), float(sm_scale), int(causal),
+                                         _ptr(O), _ptr(mask), _ptr(stats), _ptr(ws), ws.numel(), _stream()))
+    res = [O]
+    if return_mask:
+        res.append(mask)
+    if return_stats:
+        res.append(stats)
+    return res[0] if len(res) == 1 else tuple(res)

@@ -1,0 +1,275 @@
+// C ABI of libsparge: argument validation, workspace partition, kernel sequencing.
+// Nothing here allocates or synchronises; every kernel goes onto the caller's stream.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "common.hpp"
+
+using namespace sparge;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int hip_fail(hipError_t e, const char* what) {
+    return fail(SPARGE_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+size_t align256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
+
+int check_desc(const sparge_desc* d, Shape* s) {
+    if (!d) return fail(SPARGE_EINVAL, "desc is NULL");
+    if (d->B < 1 || d->H < 1 || d->N < 1) return fail(SPARGE_EINVAL, "B, H, N must be >= 1 (got %d, %d, %d)", d->B, d->H, d->N);
+    if (d->d != 64 && d->d != 128) return fail(SPARGE_EUNSUPPORTED, "head dim %d not supported (64 or 128)", d->d);
+    if (d->dtype != SPARGE_F16 && d->dtype != SPARGE_BF16) return fail(SPARGE_EUNSUPPORTED, "dtype %d not supported", d->dtype);
+    if (d->H > SPARGE_MAX_HEADS) return fail(SPARGE_EUNSUPPORTED, "H = %d exceeds %d", d->H, SPARGE_MAX_HEADS);
+    if ((long long)d->B * d->H > 65535) return fail(SPARGE_EUNSUPPORTED, "B*H exceeds 65535");
+    const int Tn = (d->N + BK - 1) / BK;
+    if (Tn > SPARGE_MAX_TN) return fail(SPARGE_EUNSUPPORTED, "N = %d gives %d key blocks, more than %d", d->N, Tn, SPARGE_MAX_TN);
+    if (d->stride_n < d->d || d->stride_b < 0 || d->stride_h < 0) return fail(SPARGE_EINVAL, "bad strides");
+    if (d->stride_n % 8 || d->stride_h % 8 || d->stride_b % 8) return fail(SPARGE_EINVAL, "strides must be multiples of 8 elements");
+    s->B = d->B; s->H = d->H; s->N = d->N; s->d = d->d; s->dtype = d->dtype;
+    s->sb = d->stride_b; s->sh = d->stride_h; s->sn = d->stride_n;
+    s->Tm = (d->N + BQ - 1) / BQ;
+    s->Tn = Tn;
+    return SPARGE_OK;
+}
+
+bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+// Partition of the scratch buffer.  Every entry point uses a subset; offsets are fixed by shape.
+struct Workspace {
+    size_t pooled_q, ksum_t, sim_q, sim_k, k_mean, logits, Qq, Kq, q_scale, k_scale, v_tiles, mask, total;
+};
+
+Workspace plan(const Shape& s, int entry) {
+    const size_t BH = (size_t)s.B * s.H;
+    const bool stats = entry == SPARGE_WS_QUANTIZE || entry == SPARGE_WS_PREDICT || entry == SPARGE_WS_ATTN ||
+                       entry == SPARGE_WS_FORWARD;
+    const bool pred = entry == SPARGE_WS_PREDICT || entry == SPARGE_WS_FORWARD;
+    const bool quant_in_ws = entry == SPARGE_WS_ATTN || entry == SPARGE_WS_FORWARD;
+    const bool attn = entry == SPARGE_WS_ATTN || entry == SPARGE_WS_ATTN_QUANTIZED || entry == SPARGE_WS_FORWARD;
+    Workspace w{};
+    size_t off = 0;
+    auto take = [&](bool used, size_t bytes) { size_t o = off; if (used) off += align256(bytes); return o; };
+    w.pooled_q = take(stats, BH * s.Tm * s.d * sizeof(double));
+    w.ksum_t = take(stats, BH * s.Tn * s.d * sizeof(double));
+    w.sim_q = take(stats, BH * s.Tm * sizeof(double));
+    w.sim_k = take(stats, BH * s.Tn * sizeof(double));
+    w.k_mean = take(quant_in_ws, BH * s.d * sizeof(float));
+    w.logits = take(pred, BH * s.Tm * s.Tn * sizeof(double));
+    w.Qq = take(quant_in_ws, BH * s.N * s.d);
+    w.Kq = take(quant_in_ws, BH * s.N * s.d);
+    w.q_scale = take(quant_in_ws, BH * s.Tm * sizeof(float));
+    w.k_scale = take(quant_in_ws, BH * s.Tn * sizeof(float));
+    w.v_tiles = take(attn, BH * s.Tn * s.d * BK * sizeof(uint16_t));
+    w.mask = take(entry == SPARGE_WS_FORWARD, BH * s.Tm * s.Tn);
+    w.total = off ? off : 256;
+    return w;
+}
+
+int check_ws(const Workspace& w, void* ws, size_t ws_bytes) {
+    if (!ws) return fail(SPARGE_EINVAL, "workspace is NULL");
+    if (reinterpret_cast<uintptr_t>(ws) & 255u) return fail(SPARGE_EINVAL, "workspace must be 256-byte aligned");
+    if (ws_bytes < w.total) return fail(SPARGE_ENOSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, w.total);
+    return SPARGE_OK;
+}
+
+template <typename T>
+T* at(void* ws, size_t off) { return reinterpret_cast<T*>(static_cast<char*>(ws) + off); }
+
+int head_params(const float* src, int H, const char* name, HeadParams* out) {
+    if (!src) return fail(SPARGE_EINVAL, "%s is NULL", name);
+    std::memset(out, 0, sizeof(*out));
+    for (int h = 0; h < H; ++h) out->v[h] = src[h];
+    return SPARGE_OK;
+}
+
+int check_tau_theta(const float* tau, const float* theta, int H, HeadParams* t, HeadParams* th) {
+    int rc;
+    if ((rc = head_params(tau, H, "tau", t))) return rc;
+    if ((rc = head_params(theta, H, "theta", th))) return rc;
+    for (int h = 0; h < H; ++h) {
+        if (!(tau[h] > 0.f && tau[h] <= 1.f)) return fail(SPARGE_EINVAL, "tau[%d] = %g outside (0,1]", h, tau[h]);
+        if (std::isnan(theta[h])) return fail(SPARGE_EINVAL, "theta[%d] is NaN", h);
+    }
+    return SPARGE_OK;
+}
+
+int check_lambda(const float* lambda, int H, HeadParams* l) {
+    int rc;
+    if ((rc = head_params(lambda, H, "lambda", l))) return rc;
+    for (int h = 0; h < H; ++h)
+        if (!(lambda[h] < 0.f)) return fail(SPARGE_EINVAL, "lambda[%d] = %g must be < 0", h, lambda[h]);
+    return SPARGE_OK;
+}
+
+// Block statistics of Q and K, Q quantization, K mean, K quantization (any output may be skipped).
+int run_stats_and_quant(const void* Q, const void* K, const Shape& s, double* pooled_q, double* ksum_t,
+                        double* sim_q, double* sim_k, int8_t* Qq, float* q_scale, int8_t* Kq, float* k_scale,
+                        float* k_mean, hipStream_t st) {
+    hipError_t e;
+    if ((e = launch_block_stats_q(Q, s, pooled_q, sim_q, Qq, q_scale, st)) != hipSuccess) return hip_fail(e, "block_stats_q");
+    if ((e = launch_block_stats_k(K, s, ksum_t, sim_k, st)) != hipSuccess) return hip_fail(e, "block_stats_k");
+    if (Kq) {
+        if ((e = launch_k_mean(ksum_t, s, k_mean, st)) != hipSuccess) return hip_fail(e, "k_mean");
+        if ((e = launch_quant_k(K, s, k_mean, Kq, k_scale, st)) != hipSuccess) return hip_fail(e, "quant_k");
+    }
+    return SPARGE_OK;
+}
+
+int run_predict(const Shape& s, void* ws, const Workspace& w, const HeadParams& tau, const HeadParams& theta,
+                float sm_scale, int causal, uint8_t* mask, hipStream_t st) {
+    hipError_t e;
+    if ((e = launch_logits(at<double>(ws, w.pooled_q), at<double>(ws, w.ksum_t), s, sm_scale,
+                           at<double>(ws, w.logits), st)) != hipSuccess) return hip_fail(e, "logits");
+    if ((e = launch_topcdf(at<double>(ws, w.logits), at<double>(ws, w.sim_q), at<double>(ws, w.sim_k), s, tau,
+                           theta, causal, mask, st)) != hipSuccess) return hip_fail(e, "topcdf");
+    return SPARGE_OK;
+}
+
+int run_attn(const int8_t* Qq, const int8_t* Kq, const float* q_scale, const float* k_scale, const void* V,
+             const Shape& s, uint16_t* v_tiles, const uint8_t* mask, const HeadParams& lam, float sm_scale,
+             int causal, void* O, uint64_t* stats, hipStream_t st) {
+    hipError_t e;
+    if ((e = launch_v_tiles(V, s, v_tiles, st)) != hipSuccess) return hip_fail(e, "v_tiles");
+    if ((e = launch_attn(Qq, Kq, q_scale, k_scale, v_tiles, s, mask, lam, sm_scale, causal, O,
+                         reinterpret_cast<unsigned long long*>(stats), st)) != hipSuccess) return hip_fail(e, "attn");
+    return SPARGE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* sparge_last_error(void) { return g_err; }
+
+int sparge_version(void) { return 100; }
+
+int sparge_workspace_bytes(const sparge_desc* desc, int entry, size_t* bytes) {
+    Shape s;
+    int rc = check_desc(desc, &s);
+    if (rc) return rc;
+    if (!bytes) return fail(SPARGE_EINVAL, "bytes is NULL");
+    if (entry < SPARGE_WS_QUANTIZE || entry > SPARGE_WS_FORWARD) return fail(SPARGE_EINVAL, "unknown entry %d", entry);
+    *bytes = plan(s, entry).total;
+    return SPARGE_OK;
+}
+
+int sparge_quantize(const void* Q, const void* K, const sparge_desc* desc, int8_t* Qq, int8_t* Kq,
+                    float* q_scale, float* k_scale, float* k_mean, void* ws, size_t ws_bytes, void* hip_stream) {
+    Shape s;
+    int rc = check_desc(desc, &s);
+    if (rc) return rc;
+    if (!Q || !K || !Qq || !Kq || !q_scale || !k_scale || !k_mean) return fail(SPARGE_EINVAL, "NULL tensor argument");
+    if (misaligned(Q) || misaligned(K) || misaligned(Qq) || misaligned(Kq) || misaligned(k_mean))
+        return fail(SPARGE_EINVAL, "tensor pointers must be 16-byte aligned");
+    const Workspace w = plan(s, SPARGE_WS_QUANTIZE);
+    if ((rc = check_ws(w, ws, ws_bytes))) return rc;
+    return run_stats_and_quant(Q, K, s, at<double>(ws, w.pooled_q), at<double>(ws, w.ksum_t), at<double>(ws, w.sim_q),
+                               at<double>(ws, w.sim_k), Qq, q_scale, Kq, k_scale, k_mean,
+                               static_cast<hipStream_t>(hip_stream));
+}
+
+int sparge_predict(const void* Q, const void* K, const sparge_desc* desc, const float* tau, const float* theta,
+                   float sm_scale, int causal, uint8_t* mask, double* sim_q, double* sim_k, void* ws,
+                   size_t ws_bytes, void* hip_stream) {
+    Shape s;
+    int rc = check_desc(desc, &s);
+    if (rc) return rc;
+    if (!Q || !K || !mask) return fail(SPARGE_EINVAL, "NULL tensor argument");
+    if (misaligned(Q) || misaligned(K)) return fail(SPARGE_EINVAL, "tensor pointers must be 16-byte aligned");
+    HeadParams t, th;
+    if ((rc = check_tau_theta(tau, theta, s.H, &t, &th))) return rc;
+    const Workspace w = plan(s, SPARGE_WS_PREDICT);
+    if ((rc = check_ws(w, ws, ws_bytes))) return rc;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if ((rc = run_stats_and_quant(Q, K, s, at<double>(ws, w.pooled_q), at<double>(ws, w.ksum_t),
+                                  at<double>(ws, w.sim_q), at<double>(ws, w.sim_k), nullptr, nullptr, nullptr,
+                                  nullptr, nullptr, st))) return rc;
+    if ((rc = run_predict(s, ws, w, t, th, sm_scale, causal, mask, st))) return rc;
+    const size_t BH = (size_t)s.B * s.H;
+    hipError_t e;
+    if (sim_q && (e = hipMemcpyAsync(sim_q, at<double>(ws, w.sim_q), BH * s.Tm * sizeof(double),
+                                     hipMemcpyDeviceToDevice, st)) != hipSuccess) return hip_fail(e, "copy sim_q");
+    if (sim_k && (e = hipMemcpyAsync(sim_k, at<double>(ws, w.sim_k), BH * s.Tn * sizeof(double),
+                                     hipMemcpyDeviceToDevice, st)) != hipSuccess) return hip_fail(e, "copy sim_k");
+    return SPARGE_OK;
+}
+
+int sparge_attn_quantized(const int8_t* Qq, const int8_t* Kq, const float* q_scale, const float* k_scale,
+                          const void* V, const sparge_desc* desc, const uint8_t* mask, const float* lambda,
+                          float sm_scale, int causal, void* O, uint64_t* stats, void* ws, size_t ws_bytes,
+                          void* hip_stream) {
+    Shape s;
+    int rc = check_desc(desc, &s);
+    if (rc) return rc;
+    if (!Qq || !Kq || !q_scale || !k_scale || !V || !O) return fail(SPARGE_EINVAL, "NULL tensor argument");
+    if (misaligned(Qq) || misaligned(Kq) || misaligned(V) || misaligned(O))
+        return fail(SPARGE_EINVAL, "tensor pointers must be 16-byte aligned");
+    HeadParams lam;
+    if ((rc = check_lambda(lambda, s.H, &lam))) return rc;
+    const Workspace w = plan(s, SPARGE_WS_ATTN_QUANTIZED);
+    if ((rc = check_ws(w, ws, ws_bytes))) return rc;
+    return run_attn(Qq, Kq, q_scale, k_scale, V, s, at<uint16_t>(ws, w.v_tiles), mask, lam, sm_scale, causal, O,
+                    stats, static_cast<hipStream_t>(hip_stream));
+}
+
+int sparge_attn(const void* Q, const void* K, const void* V, const sparge_desc* desc, const uint8_t* mask,
+                const float* lambda, float sm_scale, int causal, void* O, uint64_t* stats, void* ws,
+                size_t ws_bytes, void* hip_stream) {
+    Shape s;
+    int rc = check_desc(desc, &s);
+    if (rc) return rc;
+    if (!Q || !K || !V || !O) return fail(SPARGE_EINVAL, "NULL tensor argument");
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O))
+        return fail(SPARGE_EINVAL, "tensor pointers must be 16-byte aligned");
+    HeadParams lam;
+    if ((rc = check_lambda(lambda, s.H, &lam))) return rc;
+    const Workspace w = plan(s, SPARGE_WS_ATTN);
+    if ((rc = check_ws(w, ws, ws_bytes))) return rc;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if ((rc = run_stats_and_quant(Q, K, s, at<double>(ws, w.pooled_q), at<double>(ws, w.ksum_t),
+                                  at<double>(ws, w.sim_q), at<double>(ws, w.sim_k), at<int8_t>(ws, w.Qq),
+                                  at<float>(ws, w.q_scale), at<int8_t>(ws, w.Kq), at<float>(ws, w.k_scale),
+                                  at<float>(ws, w.k_mean), st))) return rc;
+    return run_attn(at<int8_t>(ws, w.Qq), at<int8_t>(ws, w.Kq), at<float>(ws, w.q_scale), at<float>(ws, w.k_scale),
+                    V, s, at<uint16_t>(ws, w.v_tiles), mask, lam, sm_scale, causal, O, stats, st);
+}
+
+int sparge_forward(const void* Q, const void* K, const void* V, const sparge_desc* desc, const float* tau,
+                   const float* theta, const float* lambda, float sm_scale, int causal, void* O,
+                   uint8_t* mask_out, uint64_t* stats, void* ws, size_t ws_bytes, void* hip_stream) {
+    Shape s;
+    int rc = check_desc(desc, &s);
+    if (rc) return rc;
+    if (!Q || !K || !V || !O) return fail(SPARGE_EINVAL, "NULL tensor argument");
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O))
+        return fail(SPARGE_EINVAL, "tensor pointers must be 16-byte aligned");
+    HeadParams t, th, lam;
+    if ((rc = check_tau_theta(tau, theta, s.H, &t, &th))) return rc;
+    if ((rc = check_lambda(lambda, s.H, &lam))) return rc;
+    const Workspace w = plan(s, SPARGE_WS_FORWARD);
+    if ((rc = check_ws(w, ws, ws_bytes))) return rc;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if ((rc = run_stats_and_quant(Q, K, s, at<double>(ws, w.pooled_q), at<double>(ws, w.ksum_t),
+                                  at<double>(ws, w.sim_q), at<double>(ws, w.sim_k), at<int8_t>(ws, w.Qq),
+                                  at<float>(ws, w.q_scale), at<int8_t>(ws, w.Kq), at<float>(ws, w.k_scale),
+                                  at<float>(ws, w.k_mean), st))) return rc;
+    uint8_t* mask = mask_out ? mask_out : at<uint8_t>(ws, w.mask);
+    if ((rc = run_predict(s, ws, w, t, th, sm_scale, causal, mask, st))) return rc;
+    return run_attn(at<int8_t>(ws, w.Qq), at<int8_t>(ws, w.Kq), at<float>(ws, w.q_scale), at<float>(ws, w.k_scale),
+                    V, s, at<uint16_t>(ws, w.v_tiles), mask, lam, sm_scale, causal, O, stats, st);
+}
+
+}  // extern "C"

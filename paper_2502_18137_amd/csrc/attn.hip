@@ -1,0 +1,318 @@
+// Sparse flash loop with the stage-2 filter (Alg. 1 lines 7-20; Sec. 3.1, 3.3, 3.4) for gfx950.
+//
+// Work decomposition: one workgroup of 2 waves per Q block (128 rows); a wave owns 64 query rows =
+// two 32-row groups I_w, so the stage-2 decision is wave-uniform per group.  Both matrix products
+// put the queries on the N side of a 32x32 MFMA:
+//     S^T  (keys x queries) = K_hat (A, from LDS)  x  Q_hat^T (B, registers, loaded once)
+//     O^T  (d    x queries) = V^T   (A, from LDS)  x  P~^T    (B, registers)
+// In the 32x32 accumulator layout a lane then holds one query and 16 keys (or channels), so row
+// max / row sum are in-lane reductions plus one exchange with lane^32, every per-row statistic
+// (m, l, rescale factor) is a per-lane scalar, and P~ goes from the S accumulator into the P~V
+// operand without leaving registers.  The accumulator hands a lane keys {0-3, 8-11} (lanes < 32)
+// or {4-7, 12-15} (lanes >= 32) of each group of 16; the V tiles in memory are stored in exactly
+// that slot order (see v_tiles_kernel), which is legal because a contraction index may be permuted
+// as long as both operands agree.
+#include "common.hpp"
+
+namespace sparge {
+
+namespace {
+
+constexpr float LOG2E = 1.4426950408889634f;
+
+template <int DT>
+struct PV;
+template <>
+struct PV<SPARGE_F16> {
+    typedef v8h vec;
+    static __device__ __forceinline__ v16f mfma(vec a, vec b, v16f c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ vec pack(const float* p) {
+        vec r;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) r[e] = static_cast<_Float16>(p[e]);
+        return r;
+    }
+};
+template <>
+struct PV<SPARGE_BF16> {
+    typedef v8bf vec;
+    static __device__ __forceinline__ v16f mfma(vec a, vec b, v16f c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ vec pack(const float* p) {
+        vec r;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) r[e] = static_cast<__bf16>(p[e]);
+        return r;
+    }
+};
+
+__device__ __forceinline__ float swap32(float v) { return __shfl_xor(v, 32); }
+
+template <int D, int DT, bool CAUSAL>
+__global__ __launch_bounds__(128) void attn_kernel(const int8_t* __restrict__ Qq, const int8_t* __restrict__ Kq,
+                                                    const float* __restrict__ q_scale,
+                                                    const float* __restrict__ k_scale,
+                                                    const uint16_t* __restrict__ v_tiles,
+                                                    uint16_t* __restrict__ O, const uint8_t* __restrict__ mask,
+                                                    Shape s, HeadParams lambda_h, float sm_scale, int n_work,
+                                                    int per_xcd, unsigned long long* __restrict__ stats) {
+    constexpr int KP = D + 16;        // LDS pitch of a K_hat row, bytes (16-byte pad: conflict-free b128 reads)
+    constexpr int VP = BK * 2 + 16;   // LDS pitch of a V^T row (64 key slots), bytes
+    constexpr int NSTEP = D / 32;     // int8 MFMA steps along d
+    constexpr int NDT = D / 32;       // 32-channel output tiles
+    typedef PV<DT> pv;
+
+    __shared__ __align__(16) unsigned char Ks[BK * KP];
+    __shared__ __align__(16) unsigned char Vs[D * VP];
+    __shared__ uint16_t list[SPARGE_MAX_TN];
+    __shared__ int list_cnt;
+
+    // XCD-aware work order: consecutive workgroup ids land on different XCDs, so give each XCD a
+    // contiguous range of (head, Q block) items and let its L2 serve that head's K/V tiles.
+    const int wg = blockIdx.x;
+    const int work = (wg % 8) * per_xcd + wg / 8;
+    if (work >= n_work) return;
+    const int bh = work / s.Tm;
+    const int i = CAUSAL ? (s.Tm - 1 - work % s.Tm) : (work % s.Tm);  // causal: longest rows first
+    const int b = bh / s.H, h = bh % s.H;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, hl = lane >> 5;
+
+    const int jmax = CAUSAL ? min(s.Tn, (i * BQ + BQ - 1) / BK + 1) : s.Tn;
+    // ---- kept key blocks of this row, in ascending order -------------------------------------
+    if (wave == 0) {
+        const uint8_t* mrow = mask ? mask + ((long long)bh * s.Tm + i) * s.Tn : nullptr;
+        int cnt = 0;
+        for (int base = 0; base < jmax; base += 64) {
+            const int j = base + lane;
+            const bool keep = j < jmax && (mrow ? mrow[j] != 0 : true);
+            const unsigned long long bal = __ballot(keep);
+            if (keep) list[cnt + __popcll(bal & ((1ull << lane) - 1ull))] = static_cast<uint16_t>(j);
+            cnt += __popcll(bal);
+        }
+        if (lane == 0) list_cnt = cnt;
+    }
+    __syncthreads();
+    const int cnt = list_cnt;
+
+    // ---- Q_hat fragments (B operand), resident for the whole loop ----------------------------
+    const int qrow0 = i * BQ + wave * 64;
+    v4i qf[2][NSTEP];
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+        const int row = qrow0 + g * 32 + l32;
+#pragma unroll
+        for (int st = 0; st < NSTEP; ++st) {
+            qf[g][st] = v4i{0, 0, 0, 0};
+            if (row < s.N)
+                qf[g][st] = *reinterpret_cast<const v4i*>(Qq + ((long long)bh * s.N + row) * D + st * 32 + hl * 16);
+        }
+    }
+    const float qs = q_scale[(long long)bh * s.Tm + i] * sm_scale * LOG2E;
+    const float lam2 = lambda_h.v[h] * LOG2E;
+    const float NEG = -__builtin_inff();
+
+    float m_run[2] = {NEG, NEG};
+    float l_run[2] = {0.f, 0.f};
+    v16f acc[2][NDT];
+#pragma unroll
+    for (int g = 0; g < 2; ++g)
+#pragma unroll
+        for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[g][dt][r] = 0.f;
+    int pv_done = 0;
+
+    const int8_t* kbase = Kq + (long long)bh * s.N * D;
+    const uint16_t* vbase = v_tiles + (long long)bh * s.Tn * (D * BK);
+
+    for (int t = 0; t < cnt; ++t) {
+        const int j = list[t];
+        __syncthreads();  // every wave is done reading the previous tiles
+        // ---- stage K_hat_j (64 x D int8) and V_j^T (D x 64 16-bit) in LDS --------------------
+#pragma unroll
+        for (int c = 0; c < D / 32; ++c) {
+            const int idx = tid + c * 128;
+            const int row = idx / (D / 16), col = idx % (D / 16);
+            const int key = j * BK + row;
+            v4i v = v4i{0, 0, 0, 0};
+            if (key < s.N) v = *reinterpret_cast<const v4i*>(kbase + (long long)key * D + col * 16);
+            *reinterpret_cast<v4i*>(&Ks[row * KP + col * 16]) = v;
+        }
+        const uint16_t* vt = vbase + (long long)j * (D * BK);
+#pragma unroll
+        for (int c = 0; c < D / 16; ++c) {
+            const int idx = tid + c * 128;
+            const int row = idx / 8, col = idx % 8;
+            const v4i v = *reinterpret_cast<const v4i*>(vt + row * BK + col * 8);
+            *reinterpret_cast<v4i*>(&Vs[row * VP + col * 16]) = v;
+        }
+        __syncthreads();
+
+        // ---- S^T = K_hat Q_hat^T, int32 ------------------------------------------------------
+        v16i sacc[2][2];  // [query group][key half]
+#pragma unroll
+        for (int g = 0; g < 2; ++g)
+#pragma unroll
+            for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sacc[g][kh][r] = 0;
+#pragma unroll
+        for (int kh = 0; kh < 2; ++kh) {
+#pragma unroll
+            for (int st = 0; st < NSTEP; ++st) {
+                const v4i a = *reinterpret_cast<const v4i*>(&Ks[(kh * 32 + l32) * KP + st * 32 + hl * 16]);
+                sacc[0][kh] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, qf[0][st], sacc[0][kh], 0, 0, 0);
+                sacc[1][kh] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, qf[1][st], sacc[1][kh], 0, 0, 0);
+            }
+        }
+        const float sc = qs * k_scale[(long long)bh * s.Tn + j];  // dequantization, log2 domain
+        // element masks are needed only on causal diagonal tiles and on the ragged last key block
+        const bool ragged = (j * BK + BK > s.N) || (CAUSAL && (j * BK + BK - 1 > i * BQ));
+
+#pragma unroll
+        for (int g = 0; g < 2; ++g) {
+            const int qrow = qrow0 + g * 32 + l32;
+            float p[2][16];
+            float m_loc;
+            if (!ragged) {
+                int mx = sacc[g][0][0];
+#pragma unroll
+                for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) mx = max(mx, sacc[g][kh][r]);
+                m_loc = static_cast<float>(mx) * sc;
+#pragma unroll
+                for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) p[kh][r] = static_cast<float>(sacc[g][kh][r]) * sc;
+            } else {
+                m_loc = NEG;
+#pragma unroll
+                for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int key = j * BK + kh * 32 + 8 * (r >> 2) + 4 * hl + (r & 3);
+                        const bool ok = key < s.N && (!CAUSAL || key <= qrow);
+                        const float x = ok ? static_cast<float>(sacc[g][kh][r]) * sc : NEG;
+                        p[kh][r] = x;
+                        m_loc = fmaxf(m_loc, x);
+                    }
+            }
+            m_loc = fmaxf(m_loc, swap32(m_loc));
+            const float m_new = fmaxf(m_run[g], m_loc);
+            const float m_use = (m_new == NEG) ? 0.f : m_new;
+            float rs = 0.f;
+#pragma unroll
+            for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    p[kh][r] = __builtin_amdgcn_exp2f(p[kh][r] - m_use);
+                    rs += p[kh][r];
+                }
+            const float alpha = (m_new == NEG) ? 1.f : __builtin_amdgcn_exp2f(m_run[g] - m_use);
+            l_run[g] = l_run[g] * alpha + rs;  // the row sum is always updated (Alg. 1 line 13)
+            m_run[g] = m_new;
+            // stage-2 test over the group's valid rows (Alg. 1 line 15)
+            float diff = (m_loc == NEG || qrow >= s.N) ? NEG : m_loc - m_new;
+            const bool exec = __any(diff > lam2);
+            if (exec) {
+                ++pv_done;
+                if (__any(alpha != 1.f)) {
+#pragma unroll
+                    for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) acc[g][dt][r] *= alpha;
+                }
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) {  // 16 key slots per MFMA
+                    const typename pv::vec pb = pv::pack(&p[ks >> 1][8 * (ks & 1)]);
+#pragma unroll
+                    for (int dt = 0; dt < NDT; ++dt) {
+                        const typename pv::vec va =
+                            *reinterpret_cast<const typename pv::vec*>(&Vs[(dt * 32 + l32) * VP + ks * 32 + hl * 16]);
+                        acc[g][dt] = pv::mfma(va, pb, acc[g][dt]);
+                    }
+                }
+            }
+        }
+    }
+
+    // ---- O_i = diag(l)^-1 O_i; a lane holds 4 consecutive channels per accumulator quad -------
+    uint16_t* obase = O + b * s.sb + h * s.sh;
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+        const int qrow = qrow0 + g * 32 + l32;
+        const float l_tot = l_run[g] + swap32(l_run[g]);
+        const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+        if (qrow < s.N) {
+#pragma unroll
+            for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const int c0 = dt * 32 + 8 * q4 + 4 * hl;
+                    uint16_t o[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = cvt_to16<DT>(acc[g][dt][4 * q4 + e] * inv);
+                    uint2 w;
+                    w.x = o[0] | (static_cast<uint32_t>(o[1]) << 16);
+                    w.y = o[2] | (static_cast<uint32_t>(o[3]) << 16);
+                    *reinterpret_cast<uint2*>(obase + (long long)qrow * s.sn + c0) = w;
+                }
+        }
+    }
+
+    if (stats) {
+        // row groups of this wave that exist at all
+        if (lane == 0 && pv_done) atomicAdd(&stats[bh * 4 + 1], (unsigned long long)pv_done);
+        if (tid == 0) {
+            atomicAdd(&stats[bh * 4 + 0], (unsigned long long)cnt);
+            atomicAdd(&stats[bh * 4 + 2], (unsigned long long)jmax);
+            unsigned long long vg = 0;
+            const int rows = min(BQ, s.N - i * BQ);
+            for (int g0 = 0; g0 < rows; g0 += RG) {
+                const int last_row = i * BQ + min(g0 + RG, rows) - 1;
+                vg += CAUSAL ? (unsigned long long)min(jmax, last_row / BK + 1) : (unsigned long long)jmax;
+            }
+            atomicAdd(&stats[bh * 4 + 3], vg);
+        }
+    }
+}
+
+__global__ void zero_stats_kernel(unsigned long long* stats, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) stats[i] = 0ull;
+}
+
+}  // namespace
+
+hipError_t launch_attn(const int8_t* Qq, const int8_t* Kq, const float* q_scale, const float* k_scale,
+                       const uint16_t* v_tiles, const Shape& s, const uint8_t* mask, const HeadParams& lambda,
+                       float sm_scale, int causal, void* O, unsigned long long* stats, hipStream_t st) {
+    const int n_work = s.B * s.H * s.Tm;
+    const int per_xcd = (n_work + 7) / 8;
+    dim3 grid(per_xcd * 8);
+    const float scale = sm_scale > 0.f ? sm_scale : static_cast<float>(1.0 / sqrt(static_cast<double>(s.d)));
+    if (stats) {
+        const int n = s.B * s.H * 4;
+        hipLaunchKernelGGL(zero_stats_kernel, dim3((n + 255) / 256), dim3(256), 0, st, stats, n);
+    }
+    uint16_t* o16 = static_cast<uint16_t*>(O);
+#define CALL(D, DT)                                                                                      \
+    if (causal) hipLaunchKernelGGL((attn_kernel<D, DT, true>), grid, dim3(128), 0, st, Qq, Kq, q_scale,    \
+                                   k_scale, v_tiles, o16, mask, s, lambda, scale, n_work, per_xcd, stats); \
+    else hipLaunchKernelGGL((attn_kernel<D, DT, false>), grid, dim3(128), 0, st, Qq, Kq, q_scale, k_scale, \
+                            v_tiles, o16, mask, s, lambda, scale, n_work, per_xcd, stats);
+    if (s.d == 64 && s.dtype == SPARGE_F16) { CALL(64, SPARGE_F16) }
+    else if (s.d == 64 && s.dtype == SPARGE_BF16) { CALL(64, SPARGE_BF16) }
+    else if (s.d == 128 && s.dtype == SPARGE_F16) { CALL(128, SPARGE_F16) }
+    else if (s.d == 128 && s.dtype == SPARGE_BF16) { CALL(128, SPARGE_BF16) }
+    else return hipErrorInvalidValue;
+#undef CALL
+    return hipGetLastError();
+}
+
+}  // namespace sparge

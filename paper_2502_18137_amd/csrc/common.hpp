@@ -1,0 +1,84 @@
+// Internal declarations shared by the HIP translation units of libsparge (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "sparge.h"
+
+namespace sparge {
+
+constexpr int BQ = SPARGE_BQ;         // query rows per block (Alg. 1 line 2; App. A.1)
+constexpr int BK = SPARGE_BK;         // key rows per block
+constexpr int RG = SPARGE_ROW_GROUP;  // rows per stage-2 row group (b_q / c_w)
+
+struct Shape {
+    int B, H, N, d, dtype;
+    long long sb, sh, sn;  // element strides of the 16-bit tensors
+    int Tm, Tn;
+};
+
+// Per-head scalars travel to the device inside the kernel argument block.
+struct HeadParams {
+    float v[SPARGE_MAX_HEADS];
+};
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v8f __attribute__((ext_vector_type(8)));
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
+// 16-bit storage -> fp32 (exact).  DT: SPARGE_F16 or SPARGE_BF16.
+template <int DT>
+__device__ __forceinline__ float cvt16(uint16_t bits) {
+    if constexpr (DT == SPARGE_BF16) {
+        return __uint_as_float(static_cast<uint32_t>(bits) << 16);
+    } else {
+        _Float16 h;
+        __builtin_memcpy(&h, &bits, 2);
+        return static_cast<float>(h);
+    }
+}
+
+// fp32 -> 16-bit storage, round to nearest even.
+template <int DT>
+__device__ __forceinline__ uint16_t cvt_to16(float f) {
+    uint16_t bits;
+    if constexpr (DT == SPARGE_BF16) {
+        __bf16 h = static_cast<__bf16>(f);
+        __builtin_memcpy(&bits, &h, 2);
+    } else {
+        _Float16 h = static_cast<_Float16>(f);
+        __builtin_memcpy(&bits, &h, 2);
+    }
+    return bits;
+}
+
+// ---- kernel launchers (host functions defined next to their kernels) ----------------------------
+// Block statistics of Q (+ optional INT8 quantization of Q): pooled means, self-similarity.
+hipError_t launch_block_stats_q(const void* Q, const Shape& s, double* pooled_q, double* sim_q,
+                                int8_t* Qq, float* q_scale, hipStream_t st);
+// Block statistics of K: per-block channel sums (transposed [B,H,d,Tn]) and self-similarity.
+hipError_t launch_block_stats_k(const void* K, const Shape& s, double* ksum_t, double* sim_k, hipStream_t st);
+// Token mean of K per (b,h) from the block sums.
+hipError_t launch_k_mean(const double* ksum_t, const Shape& s, float* k_mean, hipStream_t st);
+// INT8 quantization of K - k_mean.
+hipError_t launch_quant_k(const void* K, const Shape& s, const float* k_mean, int8_t* Kq, float* k_scale,
+                          hipStream_t st);
+// Compressed logits S_hat = sm_scale * q k^T (no masking), fp64 [B,H,Tm,Tn].
+hipError_t launch_logits(const double* pooled_q, const double* ksum_t, const Shape& s, float sm_scale,
+                         double* logits, hipStream_t st);
+// Softmax + TopCdf + overrides per mask row.
+hipError_t launch_topcdf(const double* logits, const double* sim_q, const double* sim_k, const Shape& s,
+                         const HeadParams& tau, const HeadParams& theta, int causal, uint8_t* mask,
+                         hipStream_t st);
+// V [B,H,N,d] (strided) -> per key block, d rows of 64 key slots in the order the P~V MFMA consumes.
+hipError_t launch_v_tiles(const void* V, const Shape& s, uint16_t* v_tiles, hipStream_t st);
+// The sparse flash loop.
+hipError_t launch_attn(const int8_t* Qq, const int8_t* Kq, const float* q_scale, const float* k_scale,
+                       const uint16_t* v_tiles, const Shape& s, const uint8_t* mask, const HeadParams& lambda,
+                       float sm_scale, int causal, void* O, unsigned long long* stats, hipStream_t st);
+
+}  // namespace sparge

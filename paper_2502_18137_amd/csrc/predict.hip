@@ -1,0 +1,211 @@
+// Stage-1 predictor after the block statistics (Alg. 1 lines 5-6; Sec. 3.2):
+//   logits : S_hat = sm_scale * q k^T on the pooled tokens, fp64 (tiny next to the attention itself)
+//   topcdf : per mask row: -inf columns, softmax, TopCdf(tau) by an in-LDS bitonic sort and a
+//            prefix sum, fix-block overrides, causal rules.
+// All arithmetic is fp64 so that block decisions agree with an fp64 reference except for
+// statistics that sit within ~1e-13 of a threshold.
+#include "common.hpp"
+
+namespace sparge {
+
+namespace {
+
+__device__ __forceinline__ double shfl_xor_f64(double v, int mask) {
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    lo = __shfl_xor(lo, mask);
+    hi = __shfl_xor(hi, mask);
+    return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ double shfl_up_f64(double v, int delta) {
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    lo = __shfl_up(lo, delta);
+    hi = __shfl_up(hi, delta);
+    return __hiloint2double(hi, lo);
+}
+
+// Thread j owns key block j; RI pooled query rows are swept per workgroup so that the transposed
+// key sums ([d][Tn], lane-coalesced) are read once per RI rows.
+template <int D, int RI>
+__global__ __launch_bounds__(256) void logits_kernel(const double* __restrict__ pooled_q,
+                                                      const double* __restrict__ ksum_t, Shape s,
+                                                      double sm_scale, double* __restrict__ logits) {
+    const long long bh = blockIdx.z;
+    const int i0 = blockIdx.y * RI;
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= s.Tn) return;
+    const double* kt = ksum_t + bh * D * s.Tn + j;
+    const double* q = pooled_q + (bh * s.Tm) * D;
+    double acc[RI];
+#pragma unroll
+    for (int r = 0; r < RI; ++r) acc[r] = 0.0;
+    for (int c = 0; c < D; ++c) {
+        const double kv = kt[(long long)c * s.Tn];
+#pragma unroll
+        for (int r = 0; r < RI; ++r) {
+            const int rr = min(i0 + r, s.Tm - 1);  // uniform: scalar loads
+            acc[r] += q[(long long)rr * D + c] * kv;
+        }
+    }
+    const double cnt = static_cast<double>(min(BK, s.N - j * BK));
+#pragma unroll
+    for (int r = 0; r < RI; ++r) {
+        if (i0 + r < s.Tm) logits[(bh * s.Tm + i0 + r) * s.Tn + j] = sm_scale * (acc[r] / cnt);
+    }
+}
+
+__device__ __forceinline__ double block_reduce(double v, bool is_max, double* scratch) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) {
+        const double o = shfl_xor_f64(v, m);
+        v = is_max ? fmax(v, o) : v + o;
+    }
+    __syncthreads();
+    if (lane == 0) scratch[wave] = v;
+    __syncthreads();
+    double r = scratch[0];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) r = is_max ? fmax(r, scratch[w]) : r + scratch[w];
+    return r;
+}
+
+// One workgroup per mask row (b, h, i).  npad = power of two >= max(Tn, 2).
+__global__ __launch_bounds__(256) void topcdf_kernel(const double* __restrict__ logits,
+                                                      const double* __restrict__ sim_q,
+                                                      const double* __restrict__ sim_k, Shape s,
+                                                      HeadParams tau_h, HeadParams theta_h, int causal,
+                                                      int npad, uint8_t* __restrict__ mask) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    double* keys = reinterpret_cast<double*>(smem);                      // [npad]
+    uint16_t* idx = reinterpret_cast<uint16_t*>(keys + npad);            // [npad]
+    uint8_t* flag = reinterpret_cast<uint8_t*>(idx + npad);              // [npad]
+    __shared__ double scratch[4];
+    __shared__ double wave_tot[4];
+
+    const int i = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const long long bh = (long long)b * s.H + h;
+    const int tid = threadIdx.x;
+    const double tau = static_cast<double>(tau_h.v[h]);
+    const double theta = static_cast<double>(theta_h.v[h]);
+    const double* row = logits + (bh * s.Tm + i) * s.Tn;
+    const double* sk = sim_k + bh * s.Tn;
+    const double NEG = -__builtin_inf();
+
+    // 1. masked logits and their maximum
+    double mx = NEG;
+    for (int j = tid; j < npad; j += 256) {
+        double x = NEG;
+        if (j < s.Tn) {
+            x = row[j];
+            if (sk[j] < theta) x = NEG;
+            if (causal && j * BK > i * BQ + (BQ - 1)) x = NEG;
+        }
+        keys[j] = x;
+        mx = fmax(mx, x);
+    }
+    mx = block_reduce(mx, true, scratch);
+    // 2. softmax numerators and their sum
+    double z = 0.0;
+    for (int j = tid; j < npad; j += 256) {
+        const double x = keys[j];
+        const double e = (x == NEG) ? 0.0 : exp(x - mx);
+        keys[j] = e;
+        z += e;
+    }
+    z = block_reduce(z, false, scratch);
+    double tot = 0.0;
+    for (int j = tid; j < npad; j += 256) {
+        double p = -1.0;  // padding ranks after every probability
+        if (j < s.Tn) {
+            p = z > 0.0 ? keys[j] / z : 0.0;
+            tot += p;
+        }
+        keys[j] = p;
+        idx[j] = static_cast<uint16_t>(j);
+        flag[j] = 0;
+    }
+    tot = block_reduce(tot, false, scratch);  // also orders the LDS writes before the sort
+
+    // 3. bitonic sort: rank order = (value descending, index ascending)
+    for (int k = 2; k <= npad; k <<= 1) {
+        for (int jj = k >> 1; jj > 0; jj >>= 1) {
+            for (int t = tid; t < (npad >> 1); t += 256) {
+                const int lo = 2 * jj * (t / jj) + (t % jj);
+                const int hi = lo + jj;
+                const double ka = keys[lo], kb = keys[hi];
+                const uint16_t ia = idx[lo], ib = idx[hi];
+                const bool a_first = (ka > kb) || (ka == kb && ia < ib);
+                const bool want_a_first = (lo & k) == 0;
+                if (a_first != want_a_first) {
+                    keys[lo] = kb; keys[hi] = ka;
+                    idx[lo] = ib; idx[hi] = ia;
+                }
+            }
+            __syncthreads();
+        }
+    }
+
+    // 4. exclusive prefix mass per rank; rank r is kept iff mass before it < tau * total
+    const int per = (npad + 255) / 256;  // consecutive ranks per thread
+    const int r0 = tid * per;
+    double local = 0.0;
+    for (int r = r0; r < min(r0 + per, npad); ++r) local += fmax(keys[r], 0.0);
+    // inclusive scan of `local` over the 256 threads
+    const int lane = tid & 63, wave = tid >> 6;
+    double incl = local;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const double o = shfl_up_f64(incl, d);
+        if (lane >= d) incl += o;
+    }
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+    double before = incl - local;
+    for (int w = 0; w < wave; ++w) before += wave_tot[w];
+    const double thresh = tau * tot;
+    for (int r = r0; r < min(r0 + per, npad); ++r) {
+        const double p = keys[r];
+        if (p > 0.0 && before < thresh) flag[idx[r]] = 1;
+        before += fmax(p, 0.0);
+    }
+    __syncthreads();
+
+    // 5. fix-block overrides and causal rules, then the row goes out
+    const bool fix_q = sim_q[bh * s.Tm + i] < theta;
+    uint8_t* out = mask + (bh * s.Tm + i) * s.Tn;
+    for (int j = tid; j < s.Tn; j += 256) {
+        uint8_t m = flag[j];
+        if (fix_q || sk[j] < theta) m = 1;
+        if (causal) {
+            if (j * BK > i * BQ + (BQ - 1)) m = 0;
+            if (j == (i * BQ) / BK) m = 1;
+        }
+        out[j] = m;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_logits(const double* pooled_q, const double* ksum_t, const Shape& s, float sm_scale,
+                         double* logits, hipStream_t st) {
+    constexpr int RI = 16;
+    dim3 grid((s.Tn + 255) / 256, (s.Tm + RI - 1) / RI, s.B * s.H);
+    const double scale = sm_scale > 0.f ? static_cast<double>(sm_scale) : 1.0 / sqrt(static_cast<double>(s.d));
+    if (s.d == 64) hipLaunchKernelGGL((logits_kernel<64, RI>), grid, dim3(256), 0, st, pooled_q, ksum_t, s, scale, logits);
+    else hipLaunchKernelGGL((logits_kernel<128, RI>), grid, dim3(256), 0, st, pooled_q, ksum_t, s, scale, logits);
+    return hipGetLastError();
+}
+
+hipError_t launch_topcdf(const double* logits, const double* sim_q, const double* sim_k, const Shape& s,
+                         const HeadParams& tau, const HeadParams& theta, int causal, uint8_t* mask,
+                         hipStream_t st) {
+    int npad = 2;
+    while (npad < s.Tn) npad <<= 1;
+    const size_t smem = static_cast<size_t>(npad) * (sizeof(double) + sizeof(uint16_t) + 1);
+    dim3 grid(s.Tm, s.H, s.B);
+    hipLaunchKernelGGL(topcdf_kernel, grid, dim3(256), smem, st, logits, sim_q, sim_k, s, tau, theta, causal,
+                       npad, mask);
+    return hipGetLastError();
+}
+
+}  // namespace sparge

@@ -1,0 +1,331 @@
+// Bandwidth-bound passes over Q and K (Alg. 1 lines 3-5):
+//   block_stats  : one read of a 128-row Q block or 64-row K block -> pooled channel sums/means,
+//                  block self-similarity CosSim, and (Q only) the per-block INT8 quantization.
+//   k_mean       : per-(batch,head) token mean of K from the block sums.
+//   quant_k      : second read of K -> INT8 of (K - mean) with per-block scales.
+//   v_tiles      : V re-tiled per 64-key block into the operand order of the P~V matrix product.
+// Thread mapping: a token row of d 16-bit values is covered by d/8 adjacent lanes holding 16 bytes
+// each, so every global load instruction moves whole 128/256-byte rows; a lane keeps the same 8
+// channels for all its rows, which makes channel sums per-lane accumulations.
+#include "common.hpp"
+
+namespace sparge {
+
+namespace {
+
+__device__ __forceinline__ double shfl_xor_f64(double v, int mask) {
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    lo = __shfl_xor(lo, mask);
+    hi = __shfl_xor(hi, mask);
+    return __hiloint2double(hi, lo);
+}
+
+template <int DT>
+__device__ __forceinline__ void unpack8(const uint4& raw, float (&f)[8]) {
+    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        f[2 * e] = cvt16<DT>(static_cast<uint16_t>(w[e] & 0xFFFFu));
+        f[2 * e + 1] = cvt16<DT>(static_cast<uint16_t>(w[e] >> 16));
+    }
+}
+
+// x_hat = rint_half_even(x * r) packed as 8 int8 (fp32 multiply, single rounding, no contraction).
+__device__ __forceinline__ uint2 quant8(const float (&f)[8], float r) {
+    uint32_t out[2] = {0u, 0u};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        float y = __builtin_rintf(f[e] * r);
+        int q = static_cast<int>(y);
+        out[e >> 2] |= (static_cast<uint32_t>(q) & 0xFFu) << (8 * (e & 3));
+    }
+    return make_uint2(out[0], out[1]);
+}
+
+// One workgroup (256 threads) per block of ROWS tokens.
+//   STATS: pooled sums + self-similarity are produced.  KSIDE: sums go out transposed and unscaled
+//   ([B,H,d,Tn], needed exactly for the K mean), otherwise means go out as [B,H,Tm,d].
+//   QUANT: the block is quantized in place from registers (Q side only).
+template <int D, int DT, int ROWS, bool KSIDE, bool QUANT>
+__global__ __launch_bounds__(256) void block_stats_kernel(const uint16_t* __restrict__ X, Shape s,
+                                                           double* __restrict__ pooled,
+                                                           double* __restrict__ sim,
+                                                           int8_t* __restrict__ Xq,
+                                                           float* __restrict__ scale) {
+    constexpr int LPR = D / 8;        // lanes per token row
+    constexpr int RPW = 64 / LPR;     // rows per wave-wide load
+    constexpr int RPS = 4 * RPW;      // rows per sweep of the 4 waves
+    constexpr int NL = ROWS / RPS;    // loads per lane
+    const int t = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int T = KSIDE ? s.Tn : s.Tm;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int cchunk = lane % LPR, rsub = lane / LPR;
+    const int row0 = t * ROWS;
+    const uint16_t* base = X + b * s.sb + h * s.sh;
+
+    __shared__ double lds_raw[4][D];
+    __shared__ double lds_hat[4][D];
+    __shared__ float lds_amax[4];
+    __shared__ double lds_sq[4];
+
+    uint4 raw[NL];
+#pragma unroll
+    for (int n = 0; n < NL; ++n) {
+        const int r = row0 + n * RPS + wave * RPW + rsub;
+        raw[n] = make_uint4(0u, 0u, 0u, 0u);
+        if (r < s.N) raw[n] = *reinterpret_cast<const uint4*>(base + (long long)r * s.sn + cchunk * 8);
+    }
+
+    double sraw[8], shat[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) sraw[e] = shat[e] = 0.0;
+    float amax = 0.f;
+#pragma unroll
+    for (int n = 0; n < NL; ++n) {
+        float f[8];
+        unpack8<DT>(raw[n], f);
+        double nsq = 0.0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const double x = static_cast<double>(f[e]);
+            nsq += x * x;
+            amax = fmaxf(amax, fabsf(f[e]));
+        }
+#pragma unroll
+        for (int m = 1; m < LPR; m <<= 1) nsq += shfl_xor_f64(nsq, m);
+        const double inv = nsq > 0.0 ? 1.0 / sqrt(nsq) : 0.0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const double x = static_cast<double>(f[e]);
+            sraw[e] += x;
+            shat[e] += x * inv;
+        }
+    }
+    // combine lanes that hold the same channels (different rows of the wave-wide load)
+#pragma unroll
+    for (int m = LPR; m < 64; m <<= 1) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            sraw[e] += shfl_xor_f64(sraw[e], m);
+            shat[e] += shfl_xor_f64(shat[e], m);
+        }
+        amax = fmaxf(amax, __shfl_xor(amax, m));
+    }
+#pragma unroll
+    for (int m = 1; m < LPR; m <<= 1) amax = fmaxf(amax, __shfl_xor(amax, m));
+    if (rsub == 0) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            lds_raw[wave][cchunk * 8 + e] = sraw[e];
+            lds_hat[wave][cchunk * 8 + e] = shat[e];
+        }
+    }
+    if (lane == 0) lds_amax[wave] = amax;
+    __syncthreads();
+
+    const int cnt = min(ROWS, s.N - row0);
+    const long long bh = (long long)b * s.H + h;
+    if (threadIdx.x < D) {
+        const int c = threadIdx.x;
+        const double rsum = ((lds_raw[0][c] + lds_raw[1][c]) + lds_raw[2][c]) + lds_raw[3][c];
+        const double hsum = ((lds_hat[0][c] + lds_hat[1][c]) + lds_hat[2][c]) + lds_hat[3][c];
+        if (KSIDE) pooled[(bh * D + c) * T + t] = rsum;
+        else pooled[(bh * T + t) * D + c] = rsum / static_cast<double>(cnt);
+        double sq = hsum * hsum;
+#pragma unroll
+        for (int m = 1; m < 64; m <<= 1) sq += shfl_xor_f64(sq, m);
+        if (lane == 0) lds_sq[wave] = sq;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double tot = lds_sq[0];
+        if (D > 64) tot += lds_sq[1];
+        sim[bh * T + t] = tot / (static_cast<double>(cnt) * static_cast<double>(cnt));
+    }
+
+    if constexpr (QUANT) {
+        const float bmax = fmaxf(fmaxf(lds_amax[0], lds_amax[1]), fmaxf(lds_amax[2], lds_amax[3]));
+        const float r = bmax > 0.f ? 127.0f / bmax : 0.f;
+        if (threadIdx.x == 0) scale[bh * T + t] = bmax > 0.f ? bmax / 127.0f : 0.f;
+        int8_t* qbase = Xq + bh * (long long)s.N * D;
+#pragma unroll
+        for (int n = 0; n < NL; ++n) {
+            const int rr = row0 + n * RPS + wave * RPW + rsub;
+            if (rr < s.N) {
+                float f[8];
+                unpack8<DT>(raw[n], f);
+                *reinterpret_cast<uint2*>(qbase + (long long)rr * D + cchunk * 8) = quant8(f, r);
+            }
+        }
+    }
+}
+
+// One workgroup per (b,h); wave w reduces channels w, w+4, ...; lanes stride over key blocks.
+template <int D>
+__global__ __launch_bounds__(256) void k_mean_kernel(const double* __restrict__ ksum_t, Shape s,
+                                                      float* __restrict__ k_mean) {
+    const long long bh = (long long)blockIdx.y * s.H + blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int c = wave; c < D; c += 4) {
+        const double* row = ksum_t + (bh * D + c) * s.Tn;
+        double acc = 0.0;
+        for (int j = lane; j < s.Tn; j += 64) acc += row[j];
+#pragma unroll
+        for (int m = 1; m < 64; m <<= 1) acc += shfl_xor_f64(acc, m);
+        if (lane == 0) k_mean[bh * D + c] = static_cast<float>(acc / static_cast<double>(s.N));
+    }
+}
+
+// One workgroup per 64-row K block: K' = fp32(K) - mean, per-block amax, INT8.
+template <int D, int DT>
+__global__ __launch_bounds__(256) void quant_k_kernel(const uint16_t* __restrict__ K, Shape s,
+                                                       const float* __restrict__ k_mean,
+                                                       int8_t* __restrict__ Kq, float* __restrict__ k_scale) {
+    constexpr int LPR = D / 8, RPW = 64 / LPR, RPS = 4 * RPW, NL = BK / RPS;
+    const int t = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int cchunk = lane % LPR, rsub = lane / LPR;
+    const int row0 = t * BK;
+    const long long bh = (long long)b * s.H + h;
+    const uint16_t* base = K + b * s.sb + h * s.sh;
+    __shared__ float lds_amax[4];
+
+    float mean[8];
+    {
+        const float4 m0 = *reinterpret_cast<const float4*>(k_mean + bh * D + cchunk * 8);
+        const float4 m1 = *reinterpret_cast<const float4*>(k_mean + bh * D + cchunk * 8 + 4);
+        mean[0] = m0.x; mean[1] = m0.y; mean[2] = m0.z; mean[3] = m0.w;
+        mean[4] = m1.x; mean[5] = m1.y; mean[6] = m1.z; mean[7] = m1.w;
+    }
+    float x[NL][8];
+    float amax = 0.f;
+#pragma unroll
+    for (int n = 0; n < NL; ++n) {
+        const int r = row0 + n * RPS + wave * RPW + rsub;
+        uint4 raw = make_uint4(0u, 0u, 0u, 0u);
+        const bool ok = r < s.N;
+        if (ok) raw = *reinterpret_cast<const uint4*>(base + (long long)r * s.sn + cchunk * 8);
+        unpack8<DT>(raw, x[n]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            x[n][e] = ok ? x[n][e] - mean[e] : 0.f;
+            amax = fmaxf(amax, fabsf(x[n][e]));
+        }
+    }
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) amax = fmaxf(amax, __shfl_xor(amax, m));
+    if (lane == 0) lds_amax[wave] = amax;
+    __syncthreads();
+    const float bmax = fmaxf(fmaxf(lds_amax[0], lds_amax[1]), fmaxf(lds_amax[2], lds_amax[3]));
+    const float r = bmax > 0.f ? 127.0f / bmax : 0.f;
+    if (threadIdx.x == 0) k_scale[bh * s.Tn + t] = bmax > 0.f ? bmax / 127.0f : 0.f;
+    int8_t* qbase = Kq + bh * (long long)s.N * D;
+#pragma unroll
+    for (int n = 0; n < NL; ++n) {
+        const int rr = row0 + n * RPS + wave * RPW + rsub;
+        if (rr < s.N) *reinterpret_cast<uint2*>(qbase + (long long)rr * D + cchunk * 8) = quant8(x[n], r);
+    }
+}
+
+// One workgroup per 64-key block: tile[c][slot] = V[key(slot)][c], 64 slots per channel row.
+// Within each group of 16 keys the slot order is {0..3, 8..11, 4..7, 12..15}: the order in which
+// the 32x32 MFMA accumulator of S^T hands a lane its keys, so P~ feeds the P~V product from
+// registers.  Keys >= N are written as zeros.
+template <int D>
+__global__ __launch_bounds__(256) void v_tiles_kernel(const uint16_t* __restrict__ V, Shape s,
+                                                       uint16_t* __restrict__ tiles) {
+    constexpr int PITCH = D + 8;  // 16-bit elements; keeps the column reads spread over LDS banks
+    __shared__ uint16_t lds[BK * PITCH];
+    const int j = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const long long bh = (long long)b * s.H + h;
+    const uint16_t* base = V + b * s.sb + h * s.sh;
+    constexpr int CPR = D / 8;  // 16-byte chunks per key row
+    for (int idx = threadIdx.x; idx < BK * CPR; idx += 256) {
+        const int row = idx / CPR, col = idx % CPR;
+        const int key = j * BK + row;
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (key < s.N) v = *reinterpret_cast<const uint4*>(base + (long long)key * s.sn + col * 8);
+        *reinterpret_cast<uint4*>(&lds[row * PITCH + col * 8]) = v;
+    }
+    __syncthreads();
+    uint16_t* out = tiles + (bh * s.Tn + j) * (long long)(D * BK);
+    for (int idx = threadIdx.x; idx < D * 8; idx += 256) {
+        const int c = idx / 8, sc = idx % 8;  // channel row, chunk of 8 slots
+        uint32_t w[4];
+#pragma unroll
+        for (int e2 = 0; e2 < 4; ++e2) {
+            uint32_t pair = 0;
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const int slot = sc * 8 + e2 * 2 + q;
+                const int g = slot >> 4, sl = slot & 15;
+                const int key = g * 16 + 8 * ((sl & 7) >> 2) + 4 * (sl >> 3) + (sl & 3);
+                pair |= static_cast<uint32_t>(lds[key * PITCH + c]) << (16 * q);
+            }
+            w[e2] = pair;
+        }
+        *reinterpret_cast<uint4*>(out + c * BK + sc * 8) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
+}  // namespace
+
+#define SPARGE_DISPATCH_D_DT(s, CALL)                                              \
+    if ((s).d == 64 && (s).dtype == SPARGE_F16) { CALL(64, SPARGE_F16) }           \
+    else if ((s).d == 64 && (s).dtype == SPARGE_BF16) { CALL(64, SPARGE_BF16) }    \
+    else if ((s).d == 128 && (s).dtype == SPARGE_F16) { CALL(128, SPARGE_F16) }    \
+    else if ((s).d == 128 && (s).dtype == SPARGE_BF16) { CALL(128, SPARGE_BF16) }  \
+    else return hipErrorInvalidValue;
+
+hipError_t launch_block_stats_q(const void* Q, const Shape& s, double* pooled_q, double* sim_q,
+                                int8_t* Qq, float* q_scale, hipStream_t st) {
+    dim3 grid(s.Tm, s.H, s.B);
+    const uint16_t* X = static_cast<const uint16_t*>(Q);
+#define CALL(D, DT)                                                                                   \
+    if (Qq) hipLaunchKernelGGL((block_stats_kernel<D, DT, BQ, false, true>), grid, dim3(256), 0, st,  \
+                               X, s, pooled_q, sim_q, Qq, q_scale);                                   \
+    else hipLaunchKernelGGL((block_stats_kernel<D, DT, BQ, false, false>), grid, dim3(256), 0, st,    \
+                            X, s, pooled_q, sim_q, Qq, q_scale);
+    SPARGE_DISPATCH_D_DT(s, CALL)
+#undef CALL
+    return hipGetLastError();
+}
+
+hipError_t launch_block_stats_k(const void* K, const Shape& s, double* ksum_t, double* sim_k, hipStream_t st) {
+    dim3 grid(s.Tn, s.H, s.B);
+    const uint16_t* X = static_cast<const uint16_t*>(K);
+#define CALL(D, DT)                                                                              \
+    hipLaunchKernelGGL((block_stats_kernel<D, DT, BK, true, false>), grid, dim3(256), 0, st, X,  \
+                       s, ksum_t, sim_k, (int8_t*)nullptr, (float*)nullptr);
+    SPARGE_DISPATCH_D_DT(s, CALL)
+#undef CALL
+    return hipGetLastError();
+}
+
+hipError_t launch_k_mean(const double* ksum_t, const Shape& s, float* k_mean, hipStream_t st) {
+    dim3 grid(s.H, s.B);
+    if (s.d == 64) hipLaunchKernelGGL((k_mean_kernel<64>), grid, dim3(256), 0, st, ksum_t, s, k_mean);
+    else hipLaunchKernelGGL((k_mean_kernel<128>), grid, dim3(256), 0, st, ksum_t, s, k_mean);
+    return hipGetLastError();
+}
+
+hipError_t launch_quant_k(const void* K, const Shape& s, const float* k_mean, int8_t* Kq, float* k_scale,
+                          hipStream_t st) {
+    dim3 grid(s.Tn, s.H, s.B);
+    const uint16_t* X = static_cast<const uint16_t*>(K);
+#define CALL(D, DT) \
+    hipLaunchKernelGGL((quant_k_kernel<D, DT>), grid, dim3(256), 0, st, X, s, k_mean, Kq, k_scale);
+    SPARGE_DISPATCH_D_DT(s, CALL)
+#undef CALL
+    return hipGetLastError();
+}
+
+hipError_t launch_v_tiles(const void* V, const Shape& s, uint16_t* v_tiles, hipStream_t st) {
+    dim3 grid(s.Tn, s.H, s.B);
+    const uint16_t* X = static_cast<const uint16_t*>(V);
+    if (s.d == 64) hipLaunchKernelGGL((v_tiles_kernel<64>), grid, dim3(256), 0, st, X, s, v_tiles);
+    else hipLaunchKernelGGL((v_tiles_kernel<128>), grid, dim3(256), 0, st, X, s, v_tiles);
+    return hipGetLastError();
+}
+
+}  // namespace sparge
