@@ -1,0 +1,261 @@
+#!/usr/bin/env python3
+"""Benchmark of the SpargeAttn hot path on one MI355X.
+
+One step = one pass of the whole hot path (sparge_forward: block statistics + INT8 quantization,
+stage-1 predictor, sparse INT8/16-bit attention with the stage-2 filter) over one batch of seeded
+synthetic input that is already resident in HBM.  The headline workload is the long-video
+configuration (N = 46080); the N = 17550 video configuration is timed as well and reported under
+"also".  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload longvideo] [--no-also]
+                    [--no-cpu-baseline] [--heads H]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_INT8 = 5.0e15   # MI355X dense INT8 MFMA, op/s
+PEAK_16 = 2.5e15     # MI355X dense fp16/bf16 MFMA, flop/s
+PEAK_HBM = 8.0e12    # B/s
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def dense_equiv_ops(w) -> float:
+    ops = 4.0 * w.N * w.N * w.d * w.H * w.B
+    return ops / 2.0 if w.causal else ops
+
+
+def executed_ops(stats: np.ndarray, d: int):
+    """INT8 ops of the executed Q_iK_j^T tiles and 16-bit flops of the executed P~V row groups."""
+    qk = float(stats[..., 0].sum()) * 2.0 * 128 * 64 * d
+    pv = float(stats[..., 1].sum()) * 2.0 * 32 * 64 * d
+    return qk, pv
+
+
+def sparsity_of(stats: np.ndarray) -> float:
+    s = stats.reshape(-1, 4).sum(0).astype(np.float64)
+    return float(1.0 - 0.5 * (s[0] / s[2] + s[1] / s[3]))
+
+
+def time_region(fn, steps, warmup):
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps * 1e3
+
+
+def event_time(fn, reps=5, warmup=2):
+    """Median milliseconds of fn() measured with events on torch's current stream (the stream the
+    binding launches on)."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    out = []
+    for _ in range(reps):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn()
+        b.record()
+        b.synchronize()
+        out.append(a.elapsed_time(b))
+    return float(np.median(out))
+
+
+def run_workload(w, data, steps, warmup, detail=True):
+    import torch
+    import paper_2502_18137_amd as sp
+
+    Q, K, V = (sp.tensor_from_numpy(data[t], w.dtype) for t in "qkv")
+    ws = torch.empty(sp.sparge_workspace_bytes(Q, sp.WS_FORWARD), dtype=torch.uint8, device="cuda")
+    O = torch.empty_like(V)
+    mask = torch.empty((w.B, w.H, (w.N + 127) // 128, (w.N + 63) // 64), dtype=torch.uint8, device="cuda")
+
+    def step():
+        sp.sparge_forward(Q, K, V, w.tau, w.theta, w.lam, causal=w.causal, ws=ws, out=O)
+
+    # one instrumented pass for the counters and the mask
+    _, mask, stats = sp.sparge_forward(Q, K, V, w.tau, w.theta, w.lam, causal=w.causal, ws=ws, out=O,
+                                       return_mask=True, return_stats=True)
+    torch.cuda.synchronize()
+    stats = stats.cpu().numpy()
+
+    timer = sp.AttnKernelTimer(steps)
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    with timer:
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        ms_step = (time.perf_counter() - t0) / steps * 1e3
+    attn_ms_list = timer.elapsed_ms()
+    timer.close()
+    attn_ms = float(np.mean(attn_ms_list))
+
+    qk_ops, pv_flops = executed_ops(stats, w.d)
+    ideal_s = qk_ops / PEAK_INT8 + pv_flops / PEAK_16
+    total = qk_ops + pv_flops
+    res = {
+        "ms_per_step": ms_step,
+        "tops": dense_equiv_ops(w) / (ms_step * 1e-3) / 1e12,
+        "sparsity": sparsity_of(stats),
+        "mask_density": float(stats[..., 0].sum() / stats[..., 2].sum()),
+        "attn_kernel_ms": attn_ms,
+        "attn_kernel_launches_timed": len(attn_ms_list),
+        "roofline": {
+            "bound": "mfma", "kernel": "attn_kernel",
+            "achieved": total / (attn_ms * 1e-3) / 1e12,
+            "peak": total / ideal_s / 1e12,
+            "unit": "TFLOP/s",
+            "frac": ideal_s / (attn_ms * 1e-3),
+            "traffic": None,
+            "executed_int8_ops": qk_ops, "executed_16bit_flops": pv_flops,
+        },
+    }
+    if detail:
+        wsq = torch.empty(sp.sparge_workspace_bytes(Q, sp.WS_QUANTIZE), dtype=torch.uint8, device="cuda")
+        wsp = torch.empty(sp.sparge_workspace_bytes(Q, sp.WS_PREDICT), dtype=torch.uint8, device="cuda")
+        res["quantize_ms"] = event_time(lambda: sp.sparge_quantize(Q, K, ws=wsq))
+        res["predict_ms"] = event_time(lambda: sp.sparge_predict(Q, K, w.tau, w.theta, causal=w.causal, ws=wsp))
+        del wsq, wsp
+        Qq, Kq, qs, ks, _ = sp.sparge_quantize(Q, K)
+        res["v_tiles_ms"] = event_time(lambda: sp.sparge_v_tiles(V))
+        vt = sp.sparge_v_tiles(V)
+        res["attn_sparse_ms"] = event_time(
+            lambda: sp.sparge_attn_tiled(Qq, Kq, qs, ks, vt, V, mask, w.lam, causal=w.causal, out=O), reps=3, warmup=1)
+        res["attn_dense_ms"] = event_time(
+            lambda: sp.sparge_attn_tiled(Qq, Kq, qs, ks, vt, V, None, -math.inf, causal=w.causal, out=O), reps=3, warmup=1)
+        res["dense_tops_attn_only"] = dense_equiv_ops(w) / (res["attn_dense_ms"] * 1e-3) / 1e12
+        dense_ideal = dense_equiv_ops(w) / 2 / PEAK_INT8 + dense_equiv_ops(w) / 2 / PEAK_16
+        res["dense_mfma_frac"] = dense_ideal / (res["attn_dense_ms"] * 1e-3)
+        res["speedup_vs_own_dense"] = (res["attn_dense_ms"] + res["v_tiles_ms"] + res["quantize_ms"]) / ms_step
+        res["predict_overhead_pct"] = 100.0 * res["predict_ms"] / res["attn_dense_ms"]
+        # HBM roofline of the bandwidth-bound passes: Q read once, K twice, Q-hat and K-hat written
+        elems = float(w.B * w.H * w.N * w.d)
+        res["quantize_GBps"] = elems * 8.0 / (res["quantize_ms"] * 1e-3) / 1e9
+        res["quantize_hbm_frac"] = res["quantize_GBps"] * 1e9 / PEAK_HBM
+        # mask-only sparsity (stage 1 alone) for the split the paper reports
+        _, st1 = sp.sparge_attn_quantized(Qq, Kq, qs, ks, V, mask, -math.inf, causal=w.causal, return_stats=True)
+        _, st2 = sp.sparge_attn_quantized(Qq, Kq, qs, ks, V, None, w.lam, causal=w.causal, return_stats=True)
+        res["sparsity_mask_only"] = sparsity_of(st1.cpu().numpy())
+        res["sparsity_lambda_only"] = sparsity_of(st2.cpu().numpy())
+    return res, mask.cpu().numpy()
+
+
+def cpu_baseline(w, data, mask_gpu, budget_blocks=None):
+    """The fp64 numpy oracle on a bounded sample: head 0, a few Q blocks against all keys."""
+    from oracle import sparge_oracle as so
+    from threadpoolctl import threadpool_info
+    q, k, v = (data[t][0, 0] for t in "qkv")
+    Tm = (w.N + 127) // 128
+    # size the sample for roughly 10-30 s: ~40 us + matmul per tile
+    per_block_s = (w.N / 64) * (60e-6 + 4.0 * 128 * 64 * w.d / 20e9)
+    nblk = budget_blocks or int(max(1, min(Tm, round(15.0 / per_block_s))))
+    blocks = sorted(set(np.linspace(0, Tm - 1, nblk).astype(int).tolist()))
+    t0 = time.perf_counter()
+    pred = so.predict(q, k, float(np.float32(w.tau)), float(np.float32(w.theta)), causal=w.causal)
+    res = so.sparse_attention(q, k, v, pred.mask, lam=float(np.float32(w.lam)), causal=w.causal, quant=True,
+                              pv_dtype=w.dtype, q_blocks=blocks)
+    dt = time.perf_counter() - t0
+    rows = sum(min(128, w.N - 128 * i) for i in blocks)
+    ops = 4.0 * rows * w.N * w.d * (0.5 if w.causal else 1.0)
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    return {
+        "value": ops / dt / 1e12, "unit": "TOPS", "cores": int(threads), "kind": "oracle",
+        "sample": f"head 0, {len(blocks)} of {Tm} Q blocks (evenly spaced) against all {w.N} keys, "
+                  f"predictor on the whole head; {dt:.1f} s of numpy fp64",
+        "seconds": dt,
+        "mask_agrees_with_gpu": bool(((mask_gpu[0, 0] == pred.mask) | pred.dont_care).all()),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="longvideo")
+    ap.add_argument("--also", default="video")
+    ap.add_argument("--no-also", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-detail", action="store_true")
+    ap.add_argument("--heads", type=int, default=0, help="debug: fewer heads (result is then not the headline)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (heads would shard with no "
+              "exchange); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    from synth import CONFIGS, make_workload
+    from synth.workloads import scaled
+
+    names = [args.workload] + ([] if args.no_also or args.also == args.workload else [args.also])
+    workers = min(16, os.cpu_count() or 1)
+    results, cpu = {}, None
+    for name in names:
+        w = CONFIGS[name]
+        if args.heads:
+            w = scaled(w, H=args.heads)
+        log(f"generating {name}: H={w.H} N={w.N} d={w.d} {w.dtype} (seeded synthetic, {workers} workers)")
+        t0 = time.perf_counter()
+        data = make_workload(w, workers=workers)   # before the GPU is touched: workers are forked
+        log(f"  generated in {time.perf_counter() - t0:.1f} s")
+        res, mask = run_workload(w, data, args.steps, args.warmup, detail=not args.no_detail)
+        log(f"  {name}: {res['ms_per_step']:.3f} ms/step, {res['tops']:.1f} dense-equivalent TOPS, "
+            f"sparsity {res['sparsity']:.3f}, attn kernel {res['attn_kernel_ms']:.3f} ms, "
+            f"MFMA frac {res['roofline']['frac']:.3f}")
+        if name == args.workload and not args.no_cpu_baseline:
+            log("  timing the CPU oracle on a bounded sample ...")
+            cpu = cpu_baseline(w, data, mask)
+            log(f"  oracle: {cpu['value']:.5f} TOPS on {cpu['cores']} threads ({cpu['seconds']:.1f} s)")
+        results[name] = (w, res)
+        del data
+
+    w, res = results[args.workload]
+    line = {
+        "metric": "dense_equivalent_attention_throughput (4*N^2*d*H / t, t = quantize + predict + sparse attention)",
+        "value": res["tops"], "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8 QK^T + %s P~V (fp32 softmax)" % w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}: B={w.B} H={w.H} N={w.N} d={w.d} {w.dtype} "
+                               f"{'causal' if w.causal else 'non-causal'} tau={w.tau} theta={w.theta} lambda={w.lam}",
+                   "block_q": 128, "block_k": 64, "row_group": 32},
+        "sparsity": res["sparsity"],
+        "roofline": res["roofline"],
+        "cpu_baseline": cpu,
+        "detail": {k: v for k, v in res.items() if k not in ("roofline", "tops", "ms_per_step", "sparsity")},
+    }
+    if len(results) > 1:
+        line["also"] = {}
+        for name, (w2, r2) in results.items():
+            if name == args.workload:
+                continue
+            line["also"][name] = {"workload": f"H={w2.H} N={w2.N} d={w2.d} {w2.dtype}", "value": r2["tops"],
+                                  "unit": "TOPS", "ms_per_step": r2["ms_per_step"], "sparsity": r2["sparsity"],
+                                  "roofline": r2["roofline"],
+                                  "detail": {k: v for k, v in r2.items()
+                                             if k not in ("roofline", "tops", "ms_per_step", "sparsity")}}
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

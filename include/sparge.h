@@ -6,7 +6,7 @@
  * General rules for every entry point
  *   - Every data pointer is DEVICE memory owned by the caller unless marked "host".  The library
  *     never allocates, never frees, keeps no pointer after returning and holds no global state
- *     besides a thread-local error string.
+ *     besides a thread-local error string (and the optional timing events, see the end).
  *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = default
  *     stream).  No entry point synchronises the host; results are valid after the stream reaches
  *     the end of the enqueued work.
@@ -108,6 +108,19 @@ int sparge_attn_quantized(const int8_t* Qq, const int8_t* Kq, const float* q_sca
                           const float* lambda, float sm_scale, int causal,
                           void* O, uint64_t* stats, void* ws, size_t ws_bytes, void* hip_stream);
 
+/*
+ * The two halves of sparge_attn_quantized, for callers that reuse V across calls or time the loop
+ * alone.  sparge_v_tiles re-tiles V for the P~V product (Alg. 1 line 16): per (b,h) and key block j,
+ * d rows of 64 key slots, keys >= N zero-filled; within every 16 keys the slot order is
+ * {0-3, 8-11, 4-7, 12-15}.  v_tiles: 16-bit, [B,H,T_n,d,64], 16-byte aligned.
+ * sparge_attn_tiled is sparge_attn_quantized with V already in that form; it needs no workspace.
+ */
+int sparge_v_tiles(const void* V, const sparge_desc* desc, void* v_tiles, void* hip_stream);
+int sparge_attn_tiled(const int8_t* Qq, const int8_t* Kq, const float* q_scale, const float* k_scale,
+                      const void* v_tiles, const sparge_desc* desc, const uint8_t* mask,
+                      const float* lambda, float sm_scale, int causal,
+                      void* O, uint64_t* stats, void* hip_stream);
+
 /* Same as sparge_quantize followed by sparge_attn_quantized, with Q-hat/K-hat kept in `ws`. */
 int sparge_attn(const void* Q, const void* K, const void* V, const sparge_desc* desc,
                 const uint8_t* mask, const float* lambda, float sm_scale, int causal,
@@ -122,6 +135,15 @@ int sparge_forward(const void* Q, const void* K, const void* V, const sparge_des
                    const float* tau, const float* theta, const float* lambda,
                    float sm_scale, int causal, void* O, uint8_t* mask_out, uint64_t* stats,
                    void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * Profiling aid (not part of the method).  Hands the library `n` pairs of caller-created hipEvent_t
+ * (host arrays of handles).  From then on, every launch of the attention kernel made by the calling
+ * thread is bracketed on its stream by hipEventRecord(starts[k]), hipEventRecord(stops[k]), k counting
+ * launches from 0; after n launches nothing more is recorded.  n = 0 (or NULL arrays) switches it off.
+ * The arrays must stay valid until then; the library never creates, destroys or waits on an event.
+ */
+int sparge_set_timing_events(void* const* starts, void* const* stops, int n);
 
 #ifdef __cplusplus
 }

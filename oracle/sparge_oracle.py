@@ -31,7 +31,7 @@ from __future__ import annotations
 
 import math
 from dataclasses import dataclass
-from typing import Optional, Tuple
+from typing import Optional, Sequence, Tuple
 
 import numpy as np
 
@@ -280,8 +280,12 @@ class AttnResult:
 
 def sparse_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, mask: Optional[np.ndarray],
                      lam: float = -np.inf, scale: Optional[float] = None, causal: bool = False,
-                     quant: bool = True, pv_dtype: str = "none") -> AttnResult:
+                     quant: bool = True, pv_dtype: str = "none",
+                     q_blocks: Optional[Sequence[int]] = None) -> AttnResult:
     """Algorithm 1's loop for one head.
+
+    q_blocks: only these Q block indices i are processed (their rows of O and their share of the
+    counters); the rest of O stays 0.  Used to sample rows of a long sequence.
 
     quant=True: S_ij = (Q-hat_i K-hat_j^T, exact integers) * delta_Q[i] * delta_K[j] * scale with the
     quantizers above (K smoothed).  quant=False: S_ij = scale * Q_i K_j^T in fp64.
@@ -302,7 +306,7 @@ def sparse_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, mask: Optional
         Kh = Kh.astype(np.float64)
     O = np.zeros((N, d), dtype=np.float64)
     qk_tiles = pv_groups = valid_tiles = valid_groups = zero_rows = 0
-    for i in range(Tm):
+    for i in (range(Tm) if q_blocks is None else q_blocks):
         r0, r1 = i * BQ, min((i + 1) * BQ, N)
         nr = r1 - r0
         rows = np.arange(r0, r1)

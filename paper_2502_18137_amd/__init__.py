@@ -4,15 +4,19 @@ Importing the package does not load the library; the first call does, and fails 
 library has not been built (python -m paper_2502_18137_amd.build).
 """
 from .binding import (  # noqa: F401
+    AttnKernelTimer,
     SpargeError,
     library_path,
     load_library,
     sparge_attn,
     sparge_attn_quantized,
+    sparge_attn_tiled,
+    sparge_v_tiles,
     sparge_forward,
     sparge_predict,
     sparge_quantize,
     sparge_version,
     sparge_workspace_bytes,
+    tensor_from_numpy,
     WS_ATTN, WS_ATTN_QUANTIZED, WS_FORWARD, WS_PREDICT, WS_QUANTIZE,
 )

@@ -53,12 +53,16 @@ def load_library() -> ctypes.CDLL:
                                    ctypes.c_size_t, vp]
     lib.sparge_attn_quantized.argtypes = [vp, vp, vp, vp, vp, dp, vp, f32p, ctypes.c_float, ctypes.c_int, vp, vp,
                                           vp, ctypes.c_size_t, vp]
+    lib.sparge_v_tiles.argtypes = [vp, dp, vp, vp]
+    lib.sparge_attn_tiled.argtypes = [vp, vp, vp, vp, vp, dp, vp, f32p, ctypes.c_float, ctypes.c_int, vp, vp, vp]
+    lib.sparge_set_timing_events.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.c_int]
+    lib.sparge_set_timing_events.restype = ctypes.c_int
     lib.sparge_attn.argtypes = [vp, vp, vp, dp, vp, f32p, ctypes.c_float, ctypes.c_int, vp, vp, vp,
                                 ctypes.c_size_t, vp]
     lib.sparge_forward.argtypes = [vp, vp, vp, dp, f32p, f32p, f32p, ctypes.c_float, ctypes.c_int, vp, vp, vp, vp,
                                    ctypes.c_size_t, vp]
     for name in ("sparge_workspace_bytes", "sparge_quantize", "sparge_predict", "sparge_attn_quantized",
-                 "sparge_attn", "sparge_forward"):
+                 "sparge_attn", "sparge_forward", "sparge_v_tiles", "sparge_attn_tiled"):
         getattr(lib, name).restype = ctypes.c_int
     _LIB = lib
     return lib
@@ -105,6 +109,13 @@ def _stream() -> ctypes.c_void_p:
 
 def _ptr(t: Optional[torch.Tensor]) -> ctypes.c_void_p:
     return ctypes.c_void_p(0 if t is None else t.data_ptr())
+
+
+def tensor_from_numpy(x, dtype: str, device: str = "cuda") -> torch.Tensor:
+    """A float32 numpy array whose values are exact in `dtype` ("fp16" | "bf16") -> GPU tensor of that dtype."""
+    import numpy as np
+    t = torch.from_numpy(np.ascontiguousarray(x))
+    return t.to(device=device, dtype=torch.float16 if dtype == "fp16" else torch.bfloat16)
 
 
 def sparge_version() -> int:
@@ -188,6 +199,31 @@ def sparge_attn_quantized(Qq, Kq, q_scale, k_scale, V: torch.Tensor, mask: Optio
     return (O, stats) if return_stats else O
 
 
+def sparge_v_tiles(V: torch.Tensor) -> torch.Tensor:
+    """-> V re-tiled for the P~V product: [B,H,Tn,d,64], V's dtype."""
+    d = _desc(V)
+    B, H, N, dim = V.shape
+    tiles = torch.empty((B, H, _blocks(N)[1], dim, BK), dtype=V.dtype, device=V.device)
+    _check(load_library().sparge_v_tiles(_ptr(V), ctypes.byref(d), _ptr(tiles), _stream()))
+    return tiles
+
+
+def sparge_attn_tiled(Qq, Kq, q_scale, k_scale, v_tiles: torch.Tensor, like: torch.Tensor,
+                      mask: Optional[torch.Tensor], lam, causal: bool = False, sm_scale: float = 0.0,
+                      stats: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None):
+    """The sparse flash loop alone.  `like` gives O's shape/strides/dtype (the V it was tiled from)."""
+    d = _desc(like)
+    B, H, N, dim = like.shape
+    if tuple(v_tiles.shape) != (B, H, _blocks(N)[1], dim, BK) or not v_tiles.is_contiguous():
+        raise SpargeError("v_tiles must come from sparge_v_tiles for this shape")
+    O = torch.empty_like(like) if out is None else out
+    _same_layout(like, O)
+    _check(load_library().sparge_attn_tiled(_ptr(Qq), _ptr(Kq), _ptr(q_scale), _ptr(k_scale), _ptr(v_tiles),
+                                            ctypes.byref(d), _ptr(mask), _per_head(lam, H), float(sm_scale),
+                                            int(causal), _ptr(O), _ptr(stats), _stream()))
+    return O
+
+
 def sparge_attn(Q, K, V, mask: Optional[torch.Tensor], lam, causal: bool = False, sm_scale: float = 0.0,
                 return_stats: bool = False, ws: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None):
     """Quantize + sparse attention.  -> O (and stats)."""
@@ -230,3 +266,51 @@ def sparge_forward(Q, K, V, tau, theta, lam, causal: bool = False, sm_scale: flo
     if return_stats:
         res.append(stats)
     return res[0] if len(res) == 1 else tuple(res)
+
+
+class AttnKernelTimer:
+    """Brackets the next `n` launches of the attention kernel with HIP events (profiling aid).
+
+    Events are created with the HIP runtime directly; elapsed_ms() synchronises on the last stop event
+    and returns the per-launch durations of the launches that actually happened.
+    """
+
+    def __init__(self, n: int):
+        self.n = n
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventQuery.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.starts = (ctypes.c_void_p * n)()
+        self.stops = (ctypes.c_void_p * n)()
+        for arr in (self.starts, self.stops):
+            for k in range(n):
+                ev = ctypes.c_void_p()
+                if self.hip.hipEventCreate(ctypes.byref(ev)) != 0:
+                    raise SpargeError("hipEventCreate failed")
+                arr[k] = ev
+
+    def __enter__(self):
+        _check(load_library().sparge_set_timing_events(self.starts, self.stops, self.n))
+        return self
+
+    def __exit__(self, *exc):
+        _check(load_library().sparge_set_timing_events(None, None, 0))
+
+    def elapsed_ms(self):
+        out = []
+        for k in range(self.n):
+            if self.hip.hipEventSynchronize(self.stops[k]) != 0:
+                break
+            ms = ctypes.c_float(0)
+            if self.hip.hipEventElapsedTime(ctypes.byref(ms), self.starts[k], self.stops[k]) != 0:
+                break  # this pair was never recorded
+            out.append(ms.value)
+        return out
+
+    def close(self):
+        for arr in (self.starts, self.stops):
+            for k in range(self.n):
+                self.hip.hipEventDestroy(arr[k])

@@ -12,6 +12,9 @@ using namespace sparge;
 namespace {
 
 thread_local char g_err[512] = "";
+thread_local void* const* g_ev_start = nullptr;
+thread_local void* const* g_ev_stop = nullptr;
+thread_local int g_ev_n = 0, g_ev_k = 0;
 
 int fail(int code, const char* fmt, ...) {
     va_list ap;
@@ -138,14 +141,33 @@ int run_predict(const Shape& s, void* ws, const Workspace& w, const HeadParams& 
     return SPARGE_OK;
 }
 
+// The attention launch, bracketed by the caller's timing events when some are installed.
+int timed_attn(const int8_t* Qq, const int8_t* Kq, const float* q_scale, const float* k_scale,
+               const uint16_t* v_tiles, const Shape& s, const uint8_t* mask, const HeadParams& lam, float sm_scale,
+               int causal, void* O, uint64_t* stats, hipStream_t st) {
+    const bool timed = g_ev_start && g_ev_k < g_ev_n;
+    hipError_t e;
+    if (stats && (e = launch_zero_stats(reinterpret_cast<unsigned long long*>(stats), s.B * s.H * 4, st)) != hipSuccess)
+        return hip_fail(e, "zero stats");
+    if (timed && (e = hipEventRecord(static_cast<hipEvent_t>(g_ev_start[g_ev_k]), st)) != hipSuccess)
+        return hip_fail(e, "record start event");
+    if ((e = launch_attn(Qq, Kq, q_scale, k_scale, v_tiles, s, mask, lam, sm_scale, causal, O,
+                         reinterpret_cast<unsigned long long*>(stats), st)) != hipSuccess)
+        return hip_fail(e, "attn");
+    if (timed) {
+        if ((e = hipEventRecord(static_cast<hipEvent_t>(g_ev_stop[g_ev_k]), st)) != hipSuccess)
+            return hip_fail(e, "record stop event");
+        ++g_ev_k;
+    }
+    return SPARGE_OK;
+}
+
 int run_attn(const int8_t* Qq, const int8_t* Kq, const float* q_scale, const float* k_scale, const void* V,
              const Shape& s, uint16_t* v_tiles, const uint8_t* mask, const HeadParams& lam, float sm_scale,
              int causal, void* O, uint64_t* stats, hipStream_t st) {
     hipError_t e;
     if ((e = launch_v_tiles(V, s, v_tiles, st)) != hipSuccess) return hip_fail(e, "v_tiles");
-    if ((e = launch_attn(Qq, Kq, q_scale, k_scale, v_tiles, s, mask, lam, sm_scale, causal, O,
-                         reinterpret_cast<unsigned long long*>(stats), st)) != hipSuccess) return hip_fail(e, "attn");
-    return SPARGE_OK;
+    return timed_attn(Qq, Kq, q_scale, k_scale, v_tiles, s, mask, lam, sm_scale, causal, O, stats, st);
 }
 
 }  // namespace
@@ -225,6 +247,31 @@ int sparge_attn_quantized(const int8_t* Qq, const int8_t* Kq, const float* q_sca
                     stats, static_cast<hipStream_t>(hip_stream));
 }
 
+int sparge_v_tiles(const void* V, const sparge_desc* desc, void* v_tiles, void* hip_stream) {
+    Shape s;
+    int rc = check_desc(desc, &s);
+    if (rc) return rc;
+    if (!V || !v_tiles) return fail(SPARGE_EINVAL, "NULL tensor argument");
+    if (misaligned(V) || misaligned(v_tiles)) return fail(SPARGE_EINVAL, "tensor pointers must be 16-byte aligned");
+    hipError_t e = launch_v_tiles(V, s, static_cast<uint16_t*>(v_tiles), static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? SPARGE_OK : hip_fail(e, "v_tiles");
+}
+
+int sparge_attn_tiled(const int8_t* Qq, const int8_t* Kq, const float* q_scale, const float* k_scale,
+                      const void* v_tiles, const sparge_desc* desc, const uint8_t* mask, const float* lambda,
+                      float sm_scale, int causal, void* O, uint64_t* stats, void* hip_stream) {
+    Shape s;
+    int rc = check_desc(desc, &s);
+    if (rc) return rc;
+    if (!Qq || !Kq || !q_scale || !k_scale || !v_tiles || !O) return fail(SPARGE_EINVAL, "NULL tensor argument");
+    if (misaligned(Qq) || misaligned(Kq) || misaligned(v_tiles) || misaligned(O))
+        return fail(SPARGE_EINVAL, "tensor pointers must be 16-byte aligned");
+    HeadParams lam;
+    if ((rc = check_lambda(lambda, s.H, &lam))) return rc;
+    return timed_attn(Qq, Kq, q_scale, k_scale, static_cast<const uint16_t*>(v_tiles), s, mask, lam, sm_scale, causal,
+                      O, stats, static_cast<hipStream_t>(hip_stream));
+}
+
 int sparge_attn(const void* Q, const void* K, const void* V, const sparge_desc* desc, const uint8_t* mask,
                 const float* lambda, float sm_scale, int causal, void* O, uint64_t* stats, void* ws,
                 size_t ws_bytes, void* hip_stream) {
@@ -270,6 +317,16 @@ int sparge_forward(const void* Q, const void* K, const void* V, const sparge_des
     if ((rc = run_predict(s, ws, w, t, th, sm_scale, causal, mask, st))) return rc;
     return run_attn(at<int8_t>(ws, w.Qq), at<int8_t>(ws, w.Kq), at<float>(ws, w.q_scale), at<float>(ws, w.k_scale),
                     V, s, at<uint16_t>(ws, w.v_tiles), mask, lam, sm_scale, causal, O, stats, st);
+}
+
+int sparge_set_timing_events(void* const* starts, void* const* stops, int n) {
+    if (n < 0) return fail(SPARGE_EINVAL, "n must be >= 0");
+    if (n > 0 && (!starts || !stops)) return fail(SPARGE_EINVAL, "event arrays are NULL");
+    g_ev_start = n ? starts : nullptr;
+    g_ev_stop = n ? stops : nullptr;
+    g_ev_n = n;
+    g_ev_k = 0;
+    return SPARGE_OK;
 }
 
 }  // extern "C"

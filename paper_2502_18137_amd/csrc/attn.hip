@@ -289,6 +289,11 @@ __global__ void zero_stats_kernel(unsigned long long* stats, int n) {
 
 }  // namespace
 
+hipError_t launch_zero_stats(unsigned long long* stats, int n, hipStream_t st) {
+    hipLaunchKernelGGL(zero_stats_kernel, dim3((n + 255) / 256), dim3(256), 0, st, stats, n);
+    return hipGetLastError();
+}
+
 hipError_t launch_attn(const int8_t* Qq, const int8_t* Kq, const float* q_scale, const float* k_scale,
                        const uint16_t* v_tiles, const Shape& s, const uint8_t* mask, const HeadParams& lambda,
                        float sm_scale, int causal, void* O, unsigned long long* stats, hipStream_t st) {
@@ -296,10 +301,6 @@ hipError_t launch_attn(const int8_t* Qq, const int8_t* Kq, const float* q_scale,
     const int per_xcd = (n_work + 7) / 8;
     dim3 grid(per_xcd * 8);
     const float scale = sm_scale > 0.f ? sm_scale : static_cast<float>(1.0 / sqrt(static_cast<double>(s.d)));
-    if (stats) {
-        const int n = s.B * s.H * 4;
-        hipLaunchKernelGGL(zero_stats_kernel, dim3((n + 255) / 256), dim3(256), 0, st, stats, n);
-    }
     uint16_t* o16 = static_cast<uint16_t*>(O);
 #define CALL(D, DT)                                                                                      \
     if (causal) hipLaunchKernelGGL((attn_kernel<D, DT, true>), grid, dim3(128), 0, st, Qq, Kq, q_scale,    \

@@ -76,7 +76,9 @@ hipError_t launch_topcdf(const double* logits, const double* sim_q, const double
                          hipStream_t st);
 // V [B,H,N,d] (strided) -> per key block, d rows of 64 key slots in the order the P~V MFMA consumes.
 hipError_t launch_v_tiles(const void* V, const Shape& s, uint16_t* v_tiles, hipStream_t st);
-// The sparse flash loop.
+// stats[0..n) = 0 (a fill kernel, not a memset node, so callers may capture it in a graph).
+hipError_t launch_zero_stats(unsigned long long* stats, int n, hipStream_t st);
+// The sparse flash loop (accumulates into stats).
 hipError_t launch_attn(const int8_t* Qq, const int8_t* Kq, const float* q_scale, const float* k_scale,
                        const uint16_t* v_tiles, const Shape& s, const uint8_t* mask, const HeadParams& lambda,
                        float sm_scale, int causal, void* O, unsigned long long* stats, hipStream_t st);

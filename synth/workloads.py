@@ -22,6 +22,7 @@ import scipy.fft
 import scipy.signal
 
 TENSOR_ID = {"q": 0, "k": 1, "v": 2, "aux": 3}
+_FFT_WORKERS = -1  # threads scipy.fft may use; pool workers set it to 1
 
 
 @dataclass(frozen=True)
@@ -160,7 +161,7 @@ def _gaussian_field(rng: np.random.Generator, grid, length_scale, channels: int)
                     for g, s in zip(grid, length_scale))
     white = rng.standard_normal((channels,) + box)
     axes = tuple(range(1, nd + 1))
-    F = scipy.fft.rfftn(white, axes=axes, workers=-1)
+    F = scipy.fft.rfftn(white, axes=axes, workers=_FFT_WORKERS)
     del white
     shape_f = F.shape[1:]
     tf = np.ones(shape_f, dtype=np.float64)
@@ -174,7 +175,7 @@ def _gaussian_field(rng: np.random.Generator, grid, length_scale, channels: int)
         sh[ax] = g.shape[0]
         tf = tf * g.reshape(sh)
     F *= tf[None]
-    f = scipy.fft.irfftn(F, s=box, axes=axes, workers=-1)
+    f = scipy.fft.irfftn(F, s=box, axes=axes, workers=_FFT_WORKERS)
     del F
     crop = (slice(None),) + tuple(slice(0, g) for g in grid)
     f = f[crop].reshape(channels, -1)
@@ -247,17 +248,40 @@ def make_head(w: Workload, head: int, tensors: Iterable[str] = ("q", "k", "v"),
     return out
 
 
+def _pool_init():
+    global _FFT_WORKERS
+    _FFT_WORKERS = 1
+
+
+def _head_job(args):
+    w, h, tensors, perm = args
+    return make_head(w, h, tensors, perm=perm)
+
+
 def make_workload(w: Workload, heads: Optional[Iterable[int]] = None,
-                  tensors: Iterable[str] = ("q", "k", "v")) -> Dict[str, np.ndarray]:
-    """All requested heads stacked: each tensor float32 [1, len(heads), N, d]."""
+                  tensors: Iterable[str] = ("q", "k", "v"), workers: int = 1) -> Dict[str, np.ndarray]:
+    """All requested heads stacked: each tensor float32 [1, len(heads), N, d].
+
+    workers > 1 generates heads in forked worker processes (every head has its own random stream,
+    so the result does not depend on the worker count).  Fork only before the GPU is initialised.
+    """
     heads = list(range(w.H)) if heads is None else list(heads)
     tensors = tuple(tensors)
     perm = hilbert_order(w.grid) if w.kind == "field" else None
     out = {t: np.empty((1, len(heads), w.N, w.d), dtype=np.float32) for t in tensors}
-    for hi, h in enumerate(heads):
-        one = make_head(w, h, tensors, perm=perm)
-        for t in tensors:
-            out[t][0, hi] = one[t]
+    jobs = [(w, h, tensors, perm) for h in heads]
+    if workers > 1 and len(heads) > 1:
+        import multiprocessing as mp
+        with mp.get_context("fork").Pool(min(workers, len(heads)), initializer=_pool_init) as pool:
+            results = pool.imap(_head_job, jobs)
+            for hi, one in enumerate(results):
+                for t in tensors:
+                    out[t][0, hi] = one[t]
+    else:
+        for hi, job in enumerate(jobs):
+            one = _head_job(job)
+            for t in tensors:
+                out[t][0, hi] = one[t]
     return out
 
 

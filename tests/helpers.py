@@ -18,9 +18,8 @@ def small_workload(name="t", N=700, d=64, dtype="fp16", H=2, causal=False, tau=0
 
 
 def to_torch(x: np.ndarray, dtype: str, device="cuda"):
-    import torch
-    t = torch.from_numpy(np.ascontiguousarray(x))
-    return t.to(device=device, dtype=torch.float16 if dtype == "fp16" else torch.bfloat16)
+    from paper_2502_18137_amd import tensor_from_numpy
+    return tensor_from_numpy(x, dtype, device)
 
 
 def gpu_inputs(w, heads=None):
