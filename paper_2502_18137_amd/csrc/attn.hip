@@ -49,24 +49,48 @@ struct PV<SPARGE_BF16> {
     }
 };
 
-__device__ __forceinline__ float swap32(float v) { return __shfl_xor(v, 32); }
+// The value held by the lane 32 positions away, combined with the own one (v_permlane32_swap).
+__device__ __forceinline__ float max_across_halves(float v) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float sum_across_halves(float v) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
 
-template <int D, int DT, bool CAUSAL>
-__global__ __launch_bounds__(128) void attn_kernel(const int8_t* __restrict__ Qq, const int8_t* __restrict__ Kq,
-                                                    const float* __restrict__ q_scale,
-                                                    const float* __restrict__ k_scale,
-                                                    const uint16_t* __restrict__ v_tiles,
-                                                    uint16_t* __restrict__ O, const uint8_t* __restrict__ mask,
-                                                    Shape s, HeadParams lambda_h, float sm_scale, int n_work,
-                                                    int per_xcd, unsigned long long* __restrict__ stats) {
-    constexpr int KP = D + 16;        // LDS pitch of a K_hat row, bytes (16-byte pad: conflict-free b128 reads)
-    constexpr int VP = BK * 2 + 16;   // LDS pitch of a V^T row (64 key slots), bytes
-    constexpr int NSTEP = D / 32;     // int8 MFMA steps along d
-    constexpr int NDT = D / 32;       // 32-channel output tiles
+// 16-byte global -> LDS copy that bypasses registers: every lane names its own global source, the
+// wave's 64 chunks land contiguously at lds_base (wave-uniform) + lane * 16.
+__device__ __forceinline__ void dma16(const void* gsrc, void* lds_base) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gsrc),
+                                     (__attribute__((address_space(3))) void*)(lds_base), 16, 0, 0);
+}
+
+// LDS tiles are unpadded; bank conflicts of the 16-byte operand reads are avoided by XOR-ing the
+// 16-byte chunk index of a row with a few row bits (applied on the global side of the copy).
+template <int ROW_BYTES>
+__device__ __forceinline__ int swz(int row) {
+    return ROW_BYTES == 128 ? ((row >> 1) & 7) : ((row >> 2) & 3);
+}
+
+// NG = 32-row query groups per wave (1 or 2); the workgroup always covers one 128-row Q block.
+template <int D, int DT, bool CAUSAL, int NG>
+__global__ __launch_bounds__(64 * (4 / NG), 2) void attn_kernel(
+    const int8_t* __restrict__ Qq, const int8_t* __restrict__ Kq, const float* __restrict__ q_scale,
+    const float* __restrict__ k_scale, const uint16_t* __restrict__ v_tiles, uint16_t* __restrict__ O,
+    const uint8_t* __restrict__ mask, Shape s, HeadParams lambda_h, float sm_scale, int n_work, int per_xcd,
+    unsigned long long* __restrict__ stats) {
+    constexpr int NW = 4 / NG;          // waves per workgroup
+    constexpr int NSTEP = D / 32;       // int8 MFMA steps along d
+    constexpr int NDT = D / 32;         // 32-channel output tiles
+    constexpr int K_BYTES = BK * D;     // K_hat tile
+    constexpr int V_BYTES = D * BK * 2; // V^T tile
+    constexpr int K_CPR = D / 16;       // 16-byte chunks per K_hat row
+    constexpr int K_DMA = K_BYTES / 1024, V_DMA = V_BYTES / 1024;  // wave-wide copies per tile
     typedef PV<DT> pv;
 
-    __shared__ __align__(16) unsigned char Ks[BK * KP];
-    __shared__ __align__(16) unsigned char Vs[D * VP];
+    __shared__ __align__(1024) unsigned char Ks[2][K_BYTES];
+    __shared__ __align__(1024) unsigned char Vs[2][V_BYTES];
     __shared__ uint16_t list[SPARGE_MAX_TN];
     __shared__ int list_cnt;
 
@@ -98,11 +122,33 @@ __global__ __launch_bounds__(128) void attn_kernel(const int8_t* __restrict__ Qq
     __syncthreads();
     const int cnt = list_cnt;
 
-    // ---- Q_hat fragments (B operand), resident for the whole loop ----------------------------
-    const int qrow0 = i * BQ + wave * 64;
-    v4i qf[2][NSTEP];
+    const int8_t* kbase = Kq + (long long)bh * s.N * D;
+    const uint16_t* vbase = v_tiles + (long long)bh * s.Tn * (D * BK);
+
+    // asynchronous copy of tile j into buffer `buf` (each wave moves its share of 1 KB pieces)
+    auto copy_tile = [&](int j, int buf) {
 #pragma unroll
-    for (int g = 0; g < 2; ++g) {
+        for (int q = wave; q < K_DMA; q += NW) {
+            const int p = q * 64 + lane;
+            const int row = p / K_CPR, phys = p % K_CPR;
+            const int key = min(j * BK + row, s.N - 1);  // rows past N repeat the last key; they are masked
+            dma16(kbase + (long long)key * D + ((phys ^ swz<D>(row)) * 16), &Ks[buf][q * 1024]);
+        }
+        const unsigned char* vt = reinterpret_cast<const unsigned char*>(vbase + (long long)j * (D * BK));
+#pragma unroll
+        for (int q = wave; q < V_DMA; q += NW) {
+            const int p = q * 64 + lane;
+            const int row = p / 8, phys = p % 8;
+            dma16(vt + row * 128 + ((phys ^ swz<128>(row)) * 16), &Vs[buf][q * 1024]);
+        }
+    };
+    if (cnt > 0) copy_tile(list[0], 0);
+
+    // ---- Q_hat fragments (B operand), resident for the whole loop ----------------------------
+    const int qrow0 = i * BQ + wave * (32 * NG);
+    v4i qf[NG][NSTEP];
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
         const int row = qrow0 + g * 32 + l32;
 #pragma unroll
         for (int st = 0; st < NSTEP; ++st) {
@@ -115,58 +161,46 @@ __global__ __launch_bounds__(128) void attn_kernel(const int8_t* __restrict__ Qq
     const float lam2 = lambda_h.v[h] * LOG2E;
     const float NEG = -__builtin_inff();
 
-    float m_run[2] = {NEG, NEG};
-    float l_run[2] = {0.f, 0.f};
-    v16f acc[2][NDT];
+    float m_run[NG], l_run[NG];
+    v16f acc[NG][NDT];
 #pragma unroll
-    for (int g = 0; g < 2; ++g)
+    for (int g = 0; g < NG; ++g) {
+        m_run[g] = NEG;
+        l_run[g] = 0.f;
 #pragma unroll
         for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[g][dt][r] = 0.f;
+    }
     int pv_done = 0;
-
-    const int8_t* kbase = Kq + (long long)bh * s.N * D;
-    const uint16_t* vbase = v_tiles + (long long)bh * s.Tn * (D * BK);
 
     for (int t = 0; t < cnt; ++t) {
         const int j = list[t];
-        __syncthreads();  // every wave is done reading the previous tiles
-        // ---- stage K_hat_j (64 x D int8) and V_j^T (D x 64 16-bit) in LDS --------------------
-#pragma unroll
-        for (int c = 0; c < D / 32; ++c) {
-            const int idx = tid + c * 128;
-            const int row = idx / (D / 16), col = idx % (D / 16);
-            const int key = j * BK + row;
-            v4i v = v4i{0, 0, 0, 0};
-            if (key < s.N) v = *reinterpret_cast<const v4i*>(kbase + (long long)key * D + col * 16);
-            *reinterpret_cast<v4i*>(&Ks[row * KP + col * 16]) = v;
-        }
-        const uint16_t* vt = vbase + (long long)j * (D * BK);
-#pragma unroll
-        for (int c = 0; c < D / 16; ++c) {
-            const int idx = tid + c * 128;
-            const int row = idx / 8, col = idx % 8;
-            const v4i v = *reinterpret_cast<const v4i*>(vt + row * BK + col * 8);
-            *reinterpret_cast<v4i*>(&Vs[row * VP + col * 16]) = v;
-        }
+        const int buf = t & 1;
+        // tile t has landed (the barrier waits for this wave's copies) and every wave has left tile
+        // t-1, whose buffer the next copy overwrites
         __syncthreads();
+        if (t + 1 < cnt) copy_tile(list[t + 1], buf ^ 1);
+        const unsigned char* Kt = Ks[buf];
+        const unsigned char* Vt = Vs[buf];
 
         // ---- S^T = K_hat Q_hat^T, int32 ------------------------------------------------------
-        v16i sacc[2][2];  // [query group][key half]
+        v16i sacc[NG][2];  // [query group][key half]
 #pragma unroll
-        for (int g = 0; g < 2; ++g)
+        for (int g = 0; g < NG; ++g)
 #pragma unroll
             for (int kh = 0; kh < 2; ++kh)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) sacc[g][kh][r] = 0;
 #pragma unroll
         for (int kh = 0; kh < 2; ++kh) {
+            const int row = kh * 32 + l32;
 #pragma unroll
             for (int st = 0; st < NSTEP; ++st) {
-                const v4i a = *reinterpret_cast<const v4i*>(&Ks[(kh * 32 + l32) * KP + st * 32 + hl * 16]);
-                sacc[0][kh] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, qf[0][st], sacc[0][kh], 0, 0, 0);
-                sacc[1][kh] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, qf[1][st], sacc[1][kh], 0, 0, 0);
+                const v4i a = *reinterpret_cast<const v4i*>(&Kt[row * D + (((st * 2 + hl) ^ swz<D>(row)) * 16)]);
+#pragma unroll
+                for (int g = 0; g < NG; ++g)
+                    sacc[g][kh] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, qf[g][st], sacc[g][kh], 0, 0, 0);
             }
         }
         const float sc = qs * k_scale[(long long)bh * s.Tn + j];  // dequantization, log2 domain
@@ -174,7 +208,7 @@ __global__ __launch_bounds__(128) void attn_kernel(const int8_t* __restrict__ Qq
         const bool ragged = (j * BK + BK > s.N) || (CAUSAL && (j * BK + BK - 1 > i * BQ));
 
 #pragma unroll
-        for (int g = 0; g < 2; ++g) {
+        for (int g = 0; g < NG; ++g) {
             const int qrow = qrow0 + g * 32 + l32;
             float p[2][16];
             float m_loc;
@@ -202,7 +236,7 @@ __global__ __launch_bounds__(128) void attn_kernel(const int8_t* __restrict__ Qq
                         m_loc = fmaxf(m_loc, x);
                     }
             }
-            m_loc = fmaxf(m_loc, swap32(m_loc));
+            m_loc = max_across_halves(m_loc);
             const float m_new = fmaxf(m_run[g], m_loc);
             const float m_use = (m_new == NEG) ? 0.f : m_new;
             float rs = 0.f;
@@ -217,7 +251,7 @@ __global__ __launch_bounds__(128) void attn_kernel(const int8_t* __restrict__ Qq
             l_run[g] = l_run[g] * alpha + rs;  // the row sum is always updated (Alg. 1 line 13)
             m_run[g] = m_new;
             // stage-2 test over the group's valid rows (Alg. 1 line 15)
-            float diff = (m_loc == NEG || qrow >= s.N) ? NEG : m_loc - m_new;
+            const float diff = (m_loc == NEG || qrow >= s.N) ? NEG : m_loc - m_new;
             const bool exec = __any(diff > lam2);
             if (exec) {
                 ++pv_done;
@@ -232,8 +266,9 @@ __global__ __launch_bounds__(128) void attn_kernel(const int8_t* __restrict__ Qq
                     const typename pv::vec pb = pv::pack(&p[ks >> 1][8 * (ks & 1)]);
 #pragma unroll
                     for (int dt = 0; dt < NDT; ++dt) {
-                        const typename pv::vec va =
-                            *reinterpret_cast<const typename pv::vec*>(&Vs[(dt * 32 + l32) * VP + ks * 32 + hl * 16]);
+                        const int row = dt * 32 + l32;
+                        const typename pv::vec va = *reinterpret_cast<const typename pv::vec*>(
+                            &Vt[row * 128 + (((ks * 2 + hl) ^ swz<128>(row)) * 16)]);
                         acc[g][dt] = pv::mfma(va, pb, acc[g][dt]);
                     }
                 }
@@ -244,9 +279,9 @@ __global__ __launch_bounds__(128) void attn_kernel(const int8_t* __restrict__ Qq
     // ---- O_i = diag(l)^-1 O_i; a lane holds 4 consecutive channels per accumulator quad -------
     uint16_t* obase = O + b * s.sb + h * s.sh;
 #pragma unroll
-    for (int g = 0; g < 2; ++g) {
+    for (int g = 0; g < NG; ++g) {
         const int qrow = qrow0 + g * 32 + l32;
-        const float l_tot = l_run[g] + swap32(l_run[g]);
+        const float l_tot = sum_across_halves(l_run[g]);
         const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
         if (qrow < s.N) {
 #pragma unroll
@@ -266,7 +301,6 @@ __global__ __launch_bounds__(128) void attn_kernel(const int8_t* __restrict__ Qq
     }
 
     if (stats) {
-        // row groups of this wave that exist at all
         if (lane == 0 && pv_done) atomicAdd(&stats[bh * 4 + 1], (unsigned long long)pv_done);
         if (tid == 0) {
             atomicAdd(&stats[bh * 4 + 0], (unsigned long long)cnt);
@@ -294,6 +328,10 @@ hipError_t launch_zero_stats(unsigned long long* stats, int n, hipStream_t st) {
     return hipGetLastError();
 }
 
+// Query groups per wave: d = 128 keeps one group per wave (4 waves, <= 256 registers, two workgroups
+// resident per SIMD set so one wave's softmax overlaps another's MFMAs); d = 64 affords two.
+template <int D> struct GroupsPerWave { static constexpr int value = 1; };
+
 hipError_t launch_attn(const int8_t* Qq, const int8_t* Kq, const float* q_scale, const float* k_scale,
                        const uint16_t* v_tiles, const Shape& s, const uint8_t* mask, const HeadParams& lambda,
                        float sm_scale, int causal, void* O, unsigned long long* stats, hipStream_t st) {
@@ -302,15 +340,19 @@ hipError_t launch_attn(const int8_t* Qq, const int8_t* Kq, const float* q_scale,
     dim3 grid(per_xcd * 8);
     const float scale = sm_scale > 0.f ? sm_scale : static_cast<float>(1.0 / sqrt(static_cast<double>(s.d)));
     uint16_t* o16 = static_cast<uint16_t*>(O);
-#define CALL(D, DT)                                                                                      \
-    if (causal) hipLaunchKernelGGL((attn_kernel<D, DT, true>), grid, dim3(128), 0, st, Qq, Kq, q_scale,    \
-                                   k_scale, v_tiles, o16, mask, s, lambda, scale, n_work, per_xcd, stats); \
-    else hipLaunchKernelGGL((attn_kernel<D, DT, false>), grid, dim3(128), 0, st, Qq, Kq, q_scale, k_scale, \
-                            v_tiles, o16, mask, s, lambda, scale, n_work, per_xcd, stats);
-    if (s.d == 64 && s.dtype == SPARGE_F16) { CALL(64, SPARGE_F16) }
-    else if (s.d == 64 && s.dtype == SPARGE_BF16) { CALL(64, SPARGE_BF16) }
-    else if (s.d == 128 && s.dtype == SPARGE_F16) { CALL(128, SPARGE_F16) }
-    else if (s.d == 128 && s.dtype == SPARGE_BF16) { CALL(128, SPARGE_BF16) }
+#define CALL(D, DT)                                                                                           \
+    {                                                                                                         \
+        constexpr int NG = GroupsPerWave<D>::value;                                                           \
+        dim3 block(64 * (4 / NG));                                                                            \
+        if (causal) hipLaunchKernelGGL((attn_kernel<D, DT, true, NG>), grid, block, 0, st, Qq, Kq, q_scale,   \
+                                       k_scale, v_tiles, o16, mask, s, lambda, scale, n_work, per_xcd, stats); \
+        else hipLaunchKernelGGL((attn_kernel<D, DT, false, NG>), grid, block, 0, st, Qq, Kq, q_scale, k_scale, \
+                                v_tiles, o16, mask, s, lambda, scale, n_work, per_xcd, stats);                \
+    }
+    if (s.d == 64 && s.dtype == SPARGE_F16) CALL(64, SPARGE_F16)
+    else if (s.d == 64 && s.dtype == SPARGE_BF16) CALL(64, SPARGE_BF16)
+    else if (s.d == 128 && s.dtype == SPARGE_F16) CALL(128, SPARGE_F16)
+    else if (s.d == 128 && s.dtype == SPARGE_BF16) CALL(128, SPARGE_BF16)
     else return hipErrorInvalidValue;
 #undef CALL
     return hipGetLastError();
