@@ -30,7 +30,9 @@ class _Desc(ctypes.Structure):
 
 
 def library_path() -> str:
-    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsparge.so")
+    """The in-tree library; SPARGE_LIBRARY overrides it (e.g. to load an experimental build)."""
+    return os.environ.get("SPARGE_LIBRARY") or os.path.join(os.path.dirname(os.path.abspath(__file__)),
+                                                            "libsparge.so")
 
 
 def load_library() -> ctypes.CDLL:

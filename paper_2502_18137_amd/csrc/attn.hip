@@ -59,12 +59,20 @@ __device__ __forceinline__ float sum_across_halves(float v) {
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-// 16-byte global -> LDS copy that bypasses registers: every lane names its own global source, the
-// wave's 64 chunks land contiguously at lds_base (wave-uniform) + lane * 16.
-__device__ __forceinline__ void dma16(const void* gsrc, void* lds_base) {
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gsrc),
-                                     (__attribute__((address_space(3))) void*)(lds_base), 16, 0, 0);
+// 16-byte global -> LDS copy that bypasses registers (LDS-DMA): every lane names its own global
+// source, the wave's 64 chunks land contiguously at the wave-uniform LDS address in M0 + lane * 16.
+// Issued through inline assembly on purpose: the compiler then does not know that the copy writes
+// LDS and so does not stall the next LDS read until the copy has landed; the kernel waits for its
+// copies itself (dma_wait) right before the barrier that publishes the tile.
+__device__ __forceinline__ void dma16(const void* gsrc, const void* lds_base) {
+    const uint32_t lds_addr =
+        static_cast<uint32_t>(reinterpret_cast<uintptr_t>((const __attribute__((address_space(3))) void*)(lds_base)));
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(gsrc), "s"(lds_addr)
+                 : "memory");
 }
+__device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // LDS tiles are unpadded; bank conflicts of the 16-byte operand reads are avoided by XOR-ing the
 // 16-byte chunk index of a row with a few row bits (applied on the global side of the copy).
@@ -102,7 +110,8 @@ __global__ __launch_bounds__(64 * (4 / NG), 2) void attn_kernel(
     const int bh = work / s.Tm;
     const int i = CAUSAL ? (s.Tm - 1 - work % s.Tm) : (work % s.Tm);  // causal: longest rows first
     const int b = bh / s.H, h = bh % s.H;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, lives in an SGPR
     const int l32 = lane & 31, hl = lane >> 5;
 
     const int jmax = CAUSAL ? min(s.Tn, (i * BQ + BQ - 1) / BK + 1) : s.Tn;
@@ -142,7 +151,7 @@ __global__ __launch_bounds__(64 * (4 / NG), 2) void attn_kernel(
             dma16(vt + row * 128 + ((phys ^ swz<128>(row)) * 16), &Vs[buf][q * 1024]);
         }
     };
-    if (cnt > 0) copy_tile(list[0], 0);
+    if (cnt > 0) copy_tile(__builtin_amdgcn_readfirstlane(list[0]), 0);
 
     // ---- Q_hat fragments (B operand), resident for the whole loop ----------------------------
     const int qrow0 = i * BQ + wave * (32 * NG);
@@ -157,6 +166,12 @@ __global__ __launch_bounds__(64 * (4 / NG), 2) void attn_kernel(
                 qf[g][st] = *reinterpret_cast<const v4i*>(Qq + ((long long)bh * s.N + row) * D + st * 32 + hl * 16);
         }
     }
+    // Pin the Q_hat loads' completion here: otherwise the compiler waits for them at their first use
+    // inside the loop with vmcnt(0), which would also wait for the tile copy just issued there.
+#pragma unroll
+    for (int g = 0; g < NG; ++g)
+#pragma unroll
+        for (int st = 0; st < NSTEP; ++st) asm volatile("" ::"v"(qf[g][st]));
     const float qs = q_scale[(long long)bh * s.Tm + i] * sm_scale * LOG2E;
     const float lam2 = lambda_h.v[h] * LOG2E;
     const float NEG = -__builtin_inff();
@@ -175,16 +190,28 @@ __global__ __launch_bounds__(64 * (4 / NG), 2) void attn_kernel(
     int pv_done = 0;
 
     for (int t = 0; t < cnt; ++t) {
-        const int j = list[t];
+        const int j = __builtin_amdgcn_readfirstlane(list[t]);
         const int buf = t & 1;
-        // tile t has landed (the barrier waits for this wave's copies) and every wave has left tile
-        // t-1, whose buffer the next copy overwrites
+        // this wave's share of tile t has landed; after the barrier all of it has, and every wave
+        // has left tile t-1, whose buffer the next copy overwrites
+        dma_wait();
         __syncthreads();
-        if (t + 1 < cnt) copy_tile(list[t + 1], buf ^ 1);
+        if (t + 1 < cnt) copy_tile(__builtin_amdgcn_readfirstlane(list[t + 1]), buf ^ 1);
         const unsigned char* Kt = Ks[buf];
         const unsigned char* Vt = Vs[buf];
+        const float sc = qs * k_scale[(long long)bh * s.Tn + j];  // dequantization, log2 domain
+        // element masks are needed only on causal diagonal tiles and on the ragged last key block
+        const bool ragged = (j * BK + BK > s.N) || (CAUSAL && (j * BK + BK - 1 > i * BQ));
 
-        // ---- S^T = K_hat Q_hat^T, int32 ------------------------------------------------------
+        // ---- S^T = K_hat Q_hat^T, int32: all operand reads first, then the MFMA chains ---------
+        v4i kf[2][NSTEP];
+#pragma unroll
+        for (int kh = 0; kh < 2; ++kh) {
+            const int row = kh * 32 + l32;
+#pragma unroll
+            for (int st = 0; st < NSTEP; ++st)
+                kf[kh][st] = *reinterpret_cast<const v4i*>(&Kt[row * D + (((st * 2 + hl) ^ swz<D>(row)) * 16)]);
+        }
         v16i sacc[NG][2];  // [query group][key half]
 #pragma unroll
         for (int g = 0; g < NG; ++g)
@@ -193,36 +220,49 @@ __global__ __launch_bounds__(64 * (4 / NG), 2) void attn_kernel(
 #pragma unroll
                 for (int r = 0; r < 16; ++r) sacc[g][kh][r] = 0;
 #pragma unroll
-        for (int kh = 0; kh < 2; ++kh) {
-            const int row = kh * 32 + l32;
+        for (int st = 0; st < NSTEP; ++st)
 #pragma unroll
-            for (int st = 0; st < NSTEP; ++st) {
-                const v4i a = *reinterpret_cast<const v4i*>(&Kt[row * D + (((st * 2 + hl) ^ swz<D>(row)) * 16)]);
+            for (int kh = 0; kh < 2; ++kh)
 #pragma unroll
                 for (int g = 0; g < NG; ++g)
-                    sacc[g][kh] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, qf[g][st], sacc[g][kh], 0, 0, 0);
-            }
-        }
-        const float sc = qs * k_scale[(long long)bh * s.Tn + j];  // dequantization, log2 domain
-        // element masks are needed only on causal diagonal tiles and on the ragged last key block
-        const bool ragged = (j * BK + BK > s.N) || (CAUSAL && (j * BK + BK - 1 > i * BQ));
+                    sacc[g][kh] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf[kh][st], qf[g][st], sacc[g][kh], 0, 0, 0);
+        // first half of the V^T operand (key slots 0..31) travels from LDS during the softmax
+        typename pv::vec vf[2][NDT];
+        auto read_v = [&](int ks0) {
+#pragma unroll
+            for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+                for (int dt = 0; dt < NDT; ++dt) {
+                    const int row = dt * 32 + l32;
+                    vf[k2][dt] = *reinterpret_cast<const typename pv::vec*>(
+                        &Vt[row * 128 + ((((ks0 + k2) * 2 + hl) ^ swz<128>(row)) * 16)]);
+                }
+        };
+        read_v(0);
+        __builtin_amdgcn_sched_barrier(0);
 
 #pragma unroll
         for (int g = 0; g < NG; ++g) {
             const int qrow = qrow0 + g * 32 + l32;
             float p[2][16];
-            float m_loc;
+            float m_loc, m_new, alpha, rs = 0.f;
             if (!ragged) {
                 int mx = sacc[g][0][0];
 #pragma unroll
                 for (int kh = 0; kh < 2; ++kh)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) mx = max(mx, sacc[g][kh][r]);
-                m_loc = static_cast<float>(mx) * sc;
+                m_loc = max_across_halves(static_cast<float>(mx) * sc);
+                m_new = fmaxf(m_run[g], m_loc);  // finite: an unmasked tile has 64 finite scores per row
+                const float nm = -m_new;
 #pragma unroll
                 for (int kh = 0; kh < 2; ++kh)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) p[kh][r] = static_cast<float>(sacc[g][kh][r]) * sc;
+                    for (int r = 0; r < 16; ++r) {
+                        p[kh][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(static_cast<float>(sacc[g][kh][r]), sc, nm));
+                        rs += p[kh][r];
+                    }
+                alpha = __builtin_amdgcn_exp2f(m_run[g] - m_new);
             } else {
                 m_loc = NEG;
 #pragma unroll
@@ -231,23 +271,21 @@ __global__ __launch_bounds__(64 * (4 / NG), 2) void attn_kernel(
                     for (int r = 0; r < 16; ++r) {
                         const int key = j * BK + kh * 32 + 8 * (r >> 2) + 4 * hl + (r & 3);
                         const bool ok = key < s.N && (!CAUSAL || key <= qrow);
-                        const float x = ok ? static_cast<float>(sacc[g][kh][r]) * sc : NEG;
-                        p[kh][r] = x;
-                        m_loc = fmaxf(m_loc, x);
+                        p[kh][r] = ok ? static_cast<float>(sacc[g][kh][r]) * sc : NEG;
+                        m_loc = fmaxf(m_loc, p[kh][r]);
                     }
+                m_loc = max_across_halves(m_loc);
+                m_new = fmaxf(m_run[g], m_loc);
+                const float m_use = (m_new == NEG) ? 0.f : m_new;
+#pragma unroll
+                for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        p[kh][r] = __builtin_amdgcn_exp2f(p[kh][r] - m_use);
+                        rs += p[kh][r];
+                    }
+                alpha = (m_new == NEG) ? 1.f : __builtin_amdgcn_exp2f(m_run[g] - m_use);
             }
-            m_loc = max_across_halves(m_loc);
-            const float m_new = fmaxf(m_run[g], m_loc);
-            const float m_use = (m_new == NEG) ? 0.f : m_new;
-            float rs = 0.f;
-#pragma unroll
-            for (int kh = 0; kh < 2; ++kh)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    p[kh][r] = __builtin_amdgcn_exp2f(p[kh][r] - m_use);
-                    rs += p[kh][r];
-                }
-            const float alpha = (m_new == NEG) ? 1.f : __builtin_amdgcn_exp2f(m_run[g] - m_use);
             l_run[g] = l_run[g] * alpha + rs;  // the row sum is always updated (Alg. 1 line 13)
             m_run[g] = m_new;
             // stage-2 test over the group's valid rows (Alg. 1 line 15)
@@ -261,17 +299,20 @@ __global__ __launch_bounds__(64 * (4 / NG), 2) void attn_kernel(
 #pragma unroll
                         for (int r = 0; r < 16; ++r) acc[g][dt][r] *= alpha;
                 }
+                typename pv::vec pb[4];
 #pragma unroll
-                for (int ks = 0; ks < 4; ++ks) {  // 16 key slots per MFMA
-                    const typename pv::vec pb = pv::pack(&p[ks >> 1][8 * (ks & 1)]);
+                for (int ks = 0; ks < 4; ++ks) pb[ks] = pv::pack(&p[ks >> 1][8 * (ks & 1)]);
+                if (NG > 1 && g > 0) read_v(0);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int dt = 0; dt < NDT; ++dt) {
-                        const int row = dt * 32 + l32;
-                        const typename pv::vec va = *reinterpret_cast<const typename pv::vec*>(
-                            &Vt[row * 128 + (((ks * 2 + hl) ^ swz<128>(row)) * 16)]);
-                        acc[g][dt] = pv::mfma(va, pb, acc[g][dt]);
-                    }
-                }
+                for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+                    for (int dt = 0; dt < NDT; ++dt) acc[g][dt] = pv::mfma(vf[k2][dt], pb[k2], acc[g][dt]);
+                read_v(2);
+#pragma unroll
+                for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+                    for (int dt = 0; dt < NDT; ++dt) acc[g][dt] = pv::mfma(vf[k2][dt], pb[2 + k2], acc[g][dt]);
             }
         }
     }
