@@ -160,20 +160,20 @@ __global__ __launch_bounds__(256) void block_stats_kernel(const uint16_t* __rest
     }
 }
 
-// One workgroup per (b,h); wave w reduces channels w, w+4, ...; lanes stride over key blocks.
+// One workgroup per (b, h, 4 channels): wave w reduces channel 4*blockIdx.x + w; lanes stride over the
+// key blocks and combine in a fixed butterfly, so the sum does not depend on scheduling.
 template <int D>
 __global__ __launch_bounds__(256) void k_mean_kernel(const double* __restrict__ ksum_t, Shape s,
                                                       float* __restrict__ k_mean) {
-    const long long bh = (long long)blockIdx.y * s.H + blockIdx.x;
+    const long long bh = (long long)blockIdx.z * s.H + blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int c = wave; c < D; c += 4) {
-        const double* row = ksum_t + (bh * D + c) * s.Tn;
-        double acc = 0.0;
-        for (int j = lane; j < s.Tn; j += 64) acc += row[j];
+    const int c = blockIdx.x * 4 + wave;
+    const double* row = ksum_t + (bh * D + c) * s.Tn;
+    double acc = 0.0;
+    for (int j = lane; j < s.Tn; j += 64) acc += row[j];
 #pragma unroll
-        for (int m = 1; m < 64; m <<= 1) acc += shfl_xor_f64(acc, m);
-        if (lane == 0) k_mean[bh * D + c] = static_cast<float>(acc / static_cast<double>(s.N));
-    }
+    for (int m = 1; m < 64; m <<= 1) acc += shfl_xor_f64(acc, m);
+    if (lane == 0) k_mean[bh * D + c] = static_cast<float>(acc / static_cast<double>(s.N));
 }
 
 // One workgroup per 64-row K block: K' = fp32(K) - mean, per-block amax, INT8.
@@ -303,7 +303,7 @@ hipError_t launch_block_stats_k(const void* K, const Shape& s, double* ksum_t, d
 }
 
 hipError_t launch_k_mean(const double* ksum_t, const Shape& s, float* k_mean, hipStream_t st) {
-    dim3 grid(s.H, s.B);
+    dim3 grid(s.d / 4, s.H, s.B);
     if (s.d == 64) hipLaunchKernelGGL((k_mean_kernel<64>), grid, dim3(256), 0, st, ksum_t, s, k_mean);
     else hipLaunchKernelGGL((k_mean_kernel<128>), grid, dim3(256), 0, st, ksum_t, s, k_mean);
     return hipGetLastError();

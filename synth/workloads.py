@@ -59,11 +59,13 @@ CONFIGS: Dict[str, Workload] = {
     "video": Workload("video", 3, H=48, N=17550, d=64, dtype="bf16", causal=False,
                       tau=0.9, theta=0.5, lam=-6.0, kind="field", grid=(13, 30, 45),
                       length_scale=(2.0, 5.0, 5.0), noise=0.2),
-    # C4: causal language-like: noise + rank-8 drifting component + sink token + recency bias.
+    # C4: causal language-like: noise + rank-8 drifting component + sink token + recency bias; the first
+    # 64 tokens (a prompt prefix holding the sink) carry no shared component, so their block is not
+    # self-similar and is always computed.
     "language": Workload("language", 4, H=32, N=32768, d=128, dtype="bf16", causal=True,
                          tau=0.95, theta=0.6, lam=-10.0, kind="language",
-                         extra={"rank": 8, "corr_len": 4096.0, "drift_gain": 2.0,
-                                "pos_gain": 1.5, "q_bias": 1.0, "sink_gain": 4.0}),
+                         extra={"rank": 8, "corr_len": 4096.0, "drift_gain": 6.0, "pos_gain": 4.0,
+                                "min_period": 512.0, "q_bias": 1.0, "sink_gain": 4.0, "prefix": 64}),
     # C5: 20x48x48 long-video grid, 3-D field (std 3 in t, 8 in h,w) + noise, Hilbert order.
     "longvideo": Workload("longvideo", 5, H=24, N=46080, d=128, dtype="bf16", causal=False,
                           tau=0.9, theta=0.5, lam=-5.0, kind="field", grid=(20, 48, 48),
@@ -230,10 +232,11 @@ def make_head(w: Workload, head: int, tensors: Iterable[str] = ("q", "k", "v"),
         eps[0] /= np.sqrt(1.0 - rho * rho)  # stationary start
         z = scipy.signal.lfilter([np.sqrt(1.0 - rho * rho)], [1.0, -rho], eps, axis=0)
         tpos = np.arange(N, dtype=np.float64)[:, None]
-        periods = 64.0 * (2.0 ** np.arange(r))[None, :]
+        periods = float(ex.get("min_period", 64.0)) * (2.0 ** np.arange(r))[None, :]
         ang = 2.0 * np.pi * tpos / periods
         p = np.concatenate([np.cos(ang), np.sin(ang)], axis=1) / np.sqrt(r)
         shared = ex["drift_gain"] * (z @ U) + ex["pos_gain"] * (p @ W)
+        shared[:int(ex.get("prefix", 0))] = 0.0  # prompt-prefix tokens carry no shared component
         for t in qk:
             rng = _rng(w, t, head)
             x = rng.standard_normal((N, d)) + shared
