@@ -217,7 +217,7 @@ def main():
             w = scaled(w, H=args.heads)
         log(f"generating {name}: H={w.H} N={w.N} d={w.d} {w.dtype} (seeded synthetic, {workers} workers)")
         t0 = time.perf_counter()
-        data = make_workload(w, workers=workers)   # before the GPU is touched: workers are forked
+        data = make_workload(w, workers=workers)
         log(f"  generated in {time.perf_counter() - t0:.1f} s")
         res, mask = run_workload(w, data, args.steps, args.warmup, detail=not args.no_detail)
         log(f"  {name}: {res['ms_per_step']:.3f} ms/step, {res['tops']:.1f} dense-equivalent TOPS, "

@@ -251,11 +251,6 @@ def make_head(w: Workload, head: int, tensors: Iterable[str] = ("q", "k", "v"),
     return out
 
 
-def _pool_init():
-    global _FFT_WORKERS
-    _FFT_WORKERS = 1
-
-
 def _head_job(args):
     w, h, tensors, perm = args
     return make_head(w, h, tensors, perm=perm)
@@ -265,26 +260,33 @@ def make_workload(w: Workload, heads: Optional[Iterable[int]] = None,
                   tensors: Iterable[str] = ("q", "k", "v"), workers: int = 1) -> Dict[str, np.ndarray]:
     """All requested heads stacked: each tensor float32 [1, len(heads), N, d].
 
-    workers > 1 generates heads in forked worker processes (every head has its own random stream,
-    so the result does not depend on the worker count).  Fork only before the GPU is initialised.
+    workers > 1 generates heads on a thread pool (numpy's generators, FFTs and array arithmetic release
+    the GIL).  Every head has its own random stream, so the result does not depend on the worker count.
     """
+    global _FFT_WORKERS
     heads = list(range(w.H)) if heads is None else list(heads)
     tensors = tuple(tensors)
     perm = hilbert_order(w.grid) if w.kind == "field" else None
     out = {t: np.empty((1, len(heads), w.N, w.d), dtype=np.float32) for t in tensors}
     jobs = [(w, h, tensors, perm) for h in heads]
+
+    def run(hi_job):
+        hi, job = hi_job
+        one = _head_job(job)
+        for t in tensors:
+            out[t][0, hi] = one[t]
+
     if workers > 1 and len(heads) > 1:
-        import multiprocessing as mp
-        with mp.get_context("fork").Pool(min(workers, len(heads)), initializer=_pool_init) as pool:
-            results = pool.imap(_head_job, jobs)
-            for hi, one in enumerate(results):
-                for t in tensors:
-                    out[t][0, hi] = one[t]
+        from concurrent.futures import ThreadPoolExecutor
+        saved, _FFT_WORKERS = _FFT_WORKERS, 1
+        try:
+            with ThreadPoolExecutor(min(workers, len(heads))) as pool:
+                list(pool.map(run, enumerate(jobs)))
+        finally:
+            _FFT_WORKERS = saved
     else:
-        for hi, job in enumerate(jobs):
-            one = _head_job(job)
-            for t in tensors:
-                out[t][0, hi] = one[t]
+        for item in enumerate(jobs):
+            run(item)
     return out
 
 

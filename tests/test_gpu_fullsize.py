@@ -1,0 +1,100 @@
+"""Parity at the full benchmark sizes, in the launch configuration bench.py times (all heads, one
+sparge_forward call).  The oracle cannot run a whole configuration, so it checks what it can compute
+one by one: for two heads the INT8 tensors, scales, K mean and block mask in full, and the output
+rows of a few evenly spaced Q blocks (first, ragged last, middle); for every head the properties that
+hold at any size (counters against the mask and against closed forms, finite output, no dead rows).
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import sparge_oracle as so
+from synth import CONFIGS, make_workload
+from tests.helpers import f32, to_torch
+
+pytestmark = pytest.mark.gpu
+
+CHECK_HEADS = 2
+Q_BLOCKS_PER_HEAD = 5
+
+
+@pytest.fixture(scope="module")
+def sp():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_2502_18137_amd as sp
+    sp.load_library()
+    return sp
+
+
+def closed_form_valid(N, causal):
+    Tm, Tn = so.nblocks(N, 128), so.nblocks(N, 64)
+    tiles = groups = 0
+    for i in range(Tm):
+        jmax = min(Tn, (i * 128 + 127) // 64 + 1) if causal else Tn
+        tiles += jmax
+        rows = min(128, N - 128 * i)
+        for g0 in range(0, rows, 32):
+            last = i * 128 + min(g0 + 32, rows) - 1
+            groups += min(jmax, last // 64 + 1) if causal else jmax
+    return tiles, groups
+
+
+@pytest.mark.parametrize("name", ["video", "language", "longvideo"])
+def test_full_configuration(sp, name):
+    import torch
+    w = CONFIGS[name]
+    print(f"generating {name}: H={w.H} N={w.N} d={w.d}", flush=True)
+    x = make_workload(w, workers=min(16, os.cpu_count() or 1))
+    Q, K, V = (to_torch(x[t], w.dtype) for t in "qkv")
+    print("running sparge_forward", flush=True)
+    O, mask, stats = sp.sparge_forward(Q, K, V, w.tau, w.theta, w.lam, causal=w.causal, return_mask=True,
+                                       return_stats=True)
+    Qq, Kq, qs, ks, km = sp.sparge_quantize(Q, K)
+    torch.cuda.synchronize()
+    mask_np, stats_np = mask.cpu().numpy(), stats.cpu().numpy()
+
+    # ---- properties for every head -----------------------------------------------------------
+    assert torch.isfinite(O.float()).all()
+    tiles, groups = closed_form_valid(w.N, w.causal)
+    assert (stats_np[0, :, 2] == tiles).all() and (stats_np[0, :, 3] == groups).all()
+    assert (stats_np[0, :, 0] == mask_np[0].reshape(w.H, -1).sum(1)).all()       # QK^T tiles = kept blocks
+    assert (stats_np[0, :, 1] <= 4 * stats_np[0, :, 0]).all()
+    assert (mask_np[0].sum(-1) >= 1).all()                                       # no Q block without keys
+    if w.causal:
+        Tm, Tn = mask_np.shape[2:]
+        future = np.triu(np.ones((Tm, Tn), dtype=bool), k=0)
+        for i in range(Tm):
+            future[i] = np.arange(Tn) * 64 > i * 128 + 127
+        assert not mask_np[0][:, future].any()
+    sparsity = 1.0 - 0.5 * (stats_np[0, :, 0].sum() / stats_np[0, :, 2].sum()
+                            + stats_np[0, :, 1].sum() / stats_np[0, :, 3].sum())
+    print(f"{name}: sparsity {sparsity:.3f}", flush=True)
+
+    # ---- element-wise checks on a few heads ----------------------------------------------------
+    Tm = so.nblocks(w.N, 128)
+    blocks = sorted(set(np.linspace(0, Tm - 1, Q_BLOCKS_PER_HEAD).astype(int).tolist()))
+    for h in (0, w.H - 1)[:CHECK_HEADS]:
+        q, k, v = x["q"][0, h], x["k"][0, h], x["v"][0, h]
+        oq, odq = so.quantize_q(q)
+        ok, odk, omean = so.quantize_k(k)
+        assert (Qq[0, h].cpu().numpy() == oq).all() and (Kq[0, h].cpu().numpy() == ok).all()
+        assert (qs[0, h].cpu().numpy().view(np.uint32) == odq.view(np.uint32)).all()
+        assert (ks[0, h].cpu().numpy().view(np.uint32) == odk.view(np.uint32)).all()
+        assert (km[0, h].cpu().numpy().view(np.uint32) == omean.view(np.uint32)).all()
+        pred = so.predict(q, k, f32(w.tau), f32(w.theta), causal=w.causal)
+        bad = (mask_np[0, h] != pred.mask) & ~pred.dont_care
+        assert not bad.any(), (h, np.argwhere(bad)[:5])
+        assert pred.dont_care.mean() < 0.01
+        # output rows of the sampled Q blocks, with the GPU's own mask so that exempt entries cannot matter
+        ref = so.sparse_attention(q, k, v, mask_np[0, h], lam=f32(w.lam), causal=w.causal, quant=True,
+                                  pv_dtype=w.dtype, q_blocks=blocks)
+        assert ref.zero_rows == 0
+        rows = np.concatenate([np.arange(128 * i, min(128 * (i + 1), w.N)) for i in blocks])
+        got = O[0, h].float().cpu().numpy().astype(np.float64)[rows]
+        err = so.rel_l1(got, so.round16(ref.O[rows], w.dtype))
+        print(f"  head {h}: {len(blocks)} Q blocks, rel-L1 vs oracle {err:.2e}, dont-care {int(pred.dont_care.sum())}",
+              flush=True)
+        assert err <= 2e-3
