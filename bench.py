@@ -27,6 +27,13 @@ sys.path.insert(0, ROOT)
 PEAK_INT8 = 5.0e15   # MI355X dense INT8 MFMA, op/s
 PEAK_16 = 2.5e15     # MI355X dense fp16/bf16 MFMA, flop/s
 PEAK_HBM = 8.0e12    # B/s
+# HBM-side bytes per launch of the attention kernel (read + written), from rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE runs of this script scaled by a 1 GiB copy (profiles/attn_kernel_hbm_traffic.txt).  They belong
+# to the default workloads with all heads; any other run reports null.
+MEASURED_TRAFFIC_BYTES = {"longvideo": 60.3e9 + 0.283e9, "video": 0.325e9 + 0.108e9}
+
+
+CONFIGS_H = {"longvideo": 24, "video": 48}
 
 
 def log(msg):
@@ -127,7 +134,8 @@ def run_workload(w, data, steps, warmup, detail=True):
             "peak": total / ideal_s / 1e12,
             "unit": "TFLOP/s",
             "frac": ideal_s / (attn_ms * 1e-3),
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if w.H == CONFIGS_H.get(w.name) else None,
+            "traffic_unit": "bytes per launch (HBM side of L2, rocprofv3 FETCH_SIZE + WRITE_SIZE)",
             "executed_int8_ops": qk_ops, "executed_16bit_flops": pv_flops,
         },
     }
@@ -199,6 +207,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-detail", action="store_true")
     ap.add_argument("--heads", type=int, default=0, help="debug: fewer heads (result is then not the headline)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one 1 GiB device-to-device copy, the known-size dispatch that HBM counter "
+                         "readings (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (heads would shard with no "
@@ -208,6 +219,13 @@ def main():
     from synth import CONFIGS, make_workload
     from synth.workloads import scaled
 
+    if args.calibration_copy:
+        import torch
+        src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")   # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     names = [args.workload] + ([] if args.no_also or args.also == args.workload else [args.also])
     workers = min(16, os.cpu_count() or 1)
     results, cpu = {}, None
