@@ -172,6 +172,8 @@ def run_workload(w, data, steps, warmup, detail=True):
 def cpu_baseline(w, data, mask_gpu, budget_blocks=None):
     """The fp64 numpy oracle on a bounded sample: head 0, a few Q blocks against all keys."""
     from oracle import sparge_oracle as so
+    import paper_2502_18137_amd as sp
+    REF_SLACK = sp.REF_SLACK_LOG2 * math.log(2.0)  # same rounding point of P~ as the kernel
     from threadpoolctl import threadpool_info
     q, k, v = (data[t][0, 0] for t in "qkv")
     Tm = (w.N + 127) // 128
@@ -182,7 +184,7 @@ def cpu_baseline(w, data, mask_gpu, budget_blocks=None):
     t0 = time.perf_counter()
     pred = so.predict(q, k, float(np.float32(w.tau)), float(np.float32(w.theta)), causal=w.causal)
     res = so.sparse_attention(q, k, v, pred.mask, lam=float(np.float32(w.lam)), causal=w.causal, quant=True,
-                              pv_dtype=w.dtype, q_blocks=blocks)
+                              pv_dtype=w.dtype, q_blocks=blocks, ref_slack=REF_SLACK)
     dt = time.perf_counter() - t0
     rows = sum(min(128, w.N - 128 * i) for i in blocks)
     ops = 4.0 * rows * w.N * w.d * (0.5 if w.causal else 1.0)

@@ -38,6 +38,8 @@ enum { SPARGE_OK = 0, SPARGE_EINVAL = -1, SPARGE_EUNSUPPORTED = -2, SPARGE_ENOSP
 enum { SPARGE_F16 = 0, SPARGE_BF16 = 1 };
 enum { SPARGE_BQ = 128, SPARGE_BK = 64, SPARGE_ROW_GROUP = 32 };
 enum { SPARGE_MAX_HEADS = 128, SPARGE_MAX_TN = 4096 };
+/* see sparge_attn_quantized: how far (log2 units) a row's maximum may run ahead of the value subtracted inside exp */
+enum { SPARGE_REF_SLACK_LOG2 = 8 };
 
 /* which entry point a workspace is sized for */
 enum { SPARGE_WS_QUANTIZE = 0, SPARGE_WS_PREDICT = 1, SPARGE_WS_ATTN = 2, SPARGE_WS_ATTN_QUANTIZED = 3,
@@ -98,6 +100,11 @@ int sparge_predict(const void* Q, const void* K, const sparge_desc* desc,
  *   for each 32-row group: if max(m_local - m_ij) > lambda:
  *       O_ij = diag(exp(m_i,j-1 - m_ij)) O_i,j-1 + P~(rounded to V's dtype) V_j   -- else skipped;
  * finally O_i = diag(l)^-1 O_i.  Rows without any kept visible key get 0.
+ * Rounding point of P~: the value subtracted inside exp is a per-row reference that lags the running
+ * maximum (O and l are kept relative to it and rescaled when it moves, which leaves O_i unchanged in
+ * real arithmetic): before a tile's softmax, if some valid row of a 32-row group has
+ * m - m_ref > SPARGE_REF_SLACK_LOG2 * ln 2, the whole group's reference moves to its running maximum.
+ * The stage-2 test always uses the running maximum m_ij itself.
  * mask: uint8 [B,H,T_m,T_n] or NULL (= all ones).  lambda: host float [H].
  * O: same dtype/strides as V (desc).  stats: optional uint64 [B,H,4] = {QK^T tiles executed,
  * P~V row-group products executed, tiles a full attention needs, row-group products a full

@@ -26,6 +26,14 @@ Readings of the paper where it is silent or ambiguous (each also listed in the d
     even, K smoothed by its per-head token mean.  The fp32 operation sequence (one reciprocal per
     block, one multiplication per element) is spelled out in
     quantize_q / quantize_k and is part of the specification.
+  * 16-bit rounding of P~ (not in the paper, whose Alg. 1 is in real arithmetic): P~ is rounded to the
+    matrix unit's input type where it enters the P~V product.  By the rescaling identity of Sec. 3.1
+    the maximum subtracted inside exp is a free reference: O and l may be kept relative to any
+    per-row reference m_ref as long as both are rescaled when it moves, and O/l does not depend on
+    it.  The loop below carries that reference explicitly.  ref_slack = 0 makes it the running
+    maximum itself at every tile (the recurrence exactly as printed); ref_slack > 0 lets it lag:
+    before a tile's softmax, if some row of a 32-row group has m - m_ref > ref_slack, the whole
+    group's reference moves to the running maximum.  Only the rounding of P~ can tell the difference.
 """
 from __future__ import annotations
 
@@ -281,7 +289,7 @@ class AttnResult:
 def sparse_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, mask: Optional[np.ndarray],
                      lam: float = -np.inf, scale: Optional[float] = None, causal: bool = False,
                      quant: bool = True, pv_dtype: str = "none",
-                     q_blocks: Optional[Sequence[int]] = None) -> AttnResult:
+                     q_blocks: Optional[Sequence[int]] = None, ref_slack: float = 0.0) -> AttnResult:
     """Algorithm 1's loop for one head.
 
     q_blocks: only these Q block indices i are processed (their rows of O and their share of the
@@ -291,6 +299,8 @@ def sparse_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, mask: Optional
     quantizers above (K smoothed).  quant=False: S_ij = scale * Q_i K_j^T in fp64.
     pv_dtype: "fp16"/"bf16" rounds P~ to that type before the P~V product (the 16-bit matrix
     unit's input); the row sum l always uses the unrounded P~.  mask=None means all ones.
+    ref_slack (natural-log units): how far the running maximum may run ahead of the reference that
+    exp subtracts (see the module header); 0 = the recurrence of Alg. 1 lines 12-16 as printed.
     """
     Q = np.asarray(Q, dtype=np.float64)
     K = np.asarray(K, dtype=np.float64)
@@ -310,7 +320,8 @@ def sparse_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, mask: Optional
         r0, r1 = i * BQ, min((i + 1) * BQ, N)
         nr = r1 - r0
         rows = np.arange(r0, r1)
-        m = np.full(nr, NEG_INF)
+        m = np.full(nr, NEG_INF)      # running maximum m_ij (Alg. 1 line 12)
+        m_ref = np.full(nr, NEG_INF)  # reference maximum that O and l are relative to
         l = np.zeros(nr)
         Oi = np.zeros((nr, d))
         for j in range(Tn):
@@ -334,13 +345,25 @@ def sparse_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, mask: Optional
                 S = np.where(cols[None, :] > rows[:, None], NEG_INF, S)
             m_local = S.max(axis=1)
             m_new = np.maximum(m, m_local)
-            live = m_new > NEG_INF
-            m_safe = np.where(live, m_new, 0.0)
+            # move the reference of every row group in which some row's maximum has run ahead of it
+            # by more than ref_slack: O and l are rescaled by exp(m_ref_old - m_ref_new) (line 13, 16)
+            moved = np.zeros(nr, dtype=bool)
+            for g0 in range(0, nr, ROW_GROUP):
+                g1 = min(g0 + ROW_GROUP, nr)
+                with np.errstate(invalid="ignore"):
+                    ahead = m_new[g0:g1] - m_ref[g0:g1]     # nan where both are -inf: no move
+                if np.any(ahead > ref_slack):
+                    with np.errstate(invalid="ignore"):
+                        f = np.exp(m_ref[g0:g1] - m_new[g0:g1])
+                    f = np.where(m_new[g0:g1] > NEG_INF, f, 1.0)
+                    l[g0:g1] *= f
+                    Oi[g0:g1] *= f[:, None]
+                    m_ref[g0:g1] = m_new[g0:g1]
+                    moved[g0:g1] = True
+            live = m_ref > NEG_INF
+            m_safe = np.where(live, m_ref, 0.0)
             P = np.exp(S - m_safe[:, None])          # exp(-inf) = 0 for masked entries
-            with np.errstate(invalid="ignore"):
-                alpha = np.exp(m - m_new)            # nan only where both are -inf (row untouched)
-            alpha = np.where(live, alpha, 1.0)
-            l = alpha * l + P.sum(axis=1)
+            l = l + P.sum(axis=1)
             Pr = round16(P, pv_dtype)
             for g0 in range(0, nr, ROW_GROUP):
                 g1 = min(g0 + ROW_GROUP, nr)
@@ -348,10 +371,10 @@ def sparse_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, mask: Optional
                     diff = np.where(m_local[g0:g1] > NEG_INF, m_local[g0:g1] - m_new[g0:g1], NEG_INF)
                 if diff.max() > lam:
                     pv_groups += 1
-                    Oi[g0:g1] = alpha[g0:g1, None] * Oi[g0:g1] + Pr[g0:g1] @ V[c0:c1]
+                    Oi[g0:g1] = Oi[g0:g1] + Pr[g0:g1] @ V[c0:c1]
                 else:
-                    # a skipped group never has a changed running max, so its rescale factor is 1
-                    assert np.all(alpha[g0:g1] == 1.0)
+                    # a skipped group never has a changed running max, so nothing was rescaled
+                    assert not moved[g0:g1].any()
             m = m_new
         dead = l == 0
         zero_rows += int(dead.sum())
@@ -400,8 +423,8 @@ def rel_l1(O: np.ndarray, O_ref: np.ndarray) -> float:
 
 def spargeattn(Q: np.ndarray, K: np.ndarray, V: np.ndarray, tau: float, theta: float, lam: float,
                causal: bool = False, scale: Optional[float] = None, quant: bool = True,
-               pv_dtype: str = "none") -> Tuple[AttnResult, Prediction]:
+               pv_dtype: str = "none", ref_slack: float = 0.0) -> Tuple[AttnResult, Prediction]:
     """The whole of Algorithm 1 for one head: Quant, predict M_g, masked loop with the lambda skip."""
     pred = predict(Q, K, tau, theta, scale, causal)
-    res = sparse_attention(Q, K, V, pred.mask, lam, scale, causal, quant, pv_dtype)
+    res = sparse_attention(Q, K, V, pred.mask, lam, scale, causal, quant, pv_dtype, ref_slack=ref_slack)
     return res, pred

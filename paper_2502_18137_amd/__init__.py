@@ -18,5 +18,6 @@ from .binding import (  # noqa: F401
     sparge_version,
     sparge_workspace_bytes,
     tensor_from_numpy,
+    REF_SLACK_LOG2,
     WS_ATTN, WS_ATTN_QUANTIZED, WS_FORWARD, WS_PREDICT, WS_QUANTIZE,
 )

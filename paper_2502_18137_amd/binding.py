@@ -15,6 +15,7 @@ import torch
 
 WS_QUANTIZE, WS_PREDICT, WS_ATTN, WS_ATTN_QUANTIZED, WS_FORWARD = range(5)
 BQ, BK = 128, 64
+REF_SLACK_LOG2 = 8  # SPARGE_REF_SLACK_LOG2 of sparge.h
 
 _LIB: Optional[ctypes.CDLL] = None
 

@@ -1,27 +1,30 @@
 #!/usr/bin/env python3
 """Writes attn_loop_gfx950.inc: the steady-state iterations of the sparse flash loop (Alg. 1 lines
 9-17 of arXiv 2502.18137 on full, unmasked tiles) as one hand-scheduled gfx950 assembly block per
-(head dimension, 16-bit type), wrapped in a C++ function that attn.hip includes.
+(head dimension, 16-bit type, LDS stages), wrapped in a C++ function that attn.hip includes.
 
     python gen_attn_loop.py            # rewrites attn_loop_gfx950.inc next to this file
 
 Why assembly: the matrix pipe and the vector ALU of a SIMD only overlap when MFMA and vector
-instructions alternate at fine grain inside one wave, and the wave owns its SIMD alone (512
-registers), so the instruction order and the register assignment are the design.  The block is
-entered at an iteration boundary of the kernel's main loop and leaves at one; everything irregular
-(first and last tiles, tiles that need element masks, skipped P~V products) stays in C++.
+instructions alternate at fine grain inside a wave, and one wave alone cannot issue vector
+instructions back to back, so the kernel runs two waves per SIMD with 256 registers each; the
+instruction order and the register assignment are the design.  The block is entered at an iteration
+boundary of the kernel's main loop and leaves at one; everything irregular (first and last tiles,
+tiles that need element masks, skipped P~V products, moving the reference maximum) stays in C++.
 
-State at the boundary "top of iteration u" (u >= 1; tiles are positions in the row's kept list):
-  group A: P~ of tile u-1 waits for its P~V product (execA = its stage-2 decision);
-  group B: biased scores S of tile u-1 wait for their softmax (scB = their dequantization scale,
-           execB = their stage-2 decision); all row statistics are up to date;
-  LDS:     K_hat(u) and V(u-1) have been requested NST-1 iterations ago.
-Iteration u:  wait for own copies, barrier, request K_hat(u+NST-1) and V(u+NST-2), then
-  step 1: softmax of (B, u-1) on the vector ALU  |  MFMA: scores of (A, u), P~V of (A, u-1)
-  step 2: softmax of (A, u)                      |  MFMA: scores of (B, u), P~V of (B, u-1)
-Each step is a sequence of slots: operand read (LDS, three slots ahead), one MFMA, a chunk of the
-softmax.  The row maximum of the fresh scores, the stage-2 test (Alg. 1 line 15) and the test
-whether the reference maximum must move follow at the end of the step.
+A wave owns one 32-row group.  The loop is skewed by one tile; tiles are positions in the row's list
+of kept key blocks.  State at the boundary "top of iteration u" (u >= 1):
+  S[u & 1]        biased scores of tile u; the row statistics already include tile u
+                  (scx = its dequantization scale, exec = its stage-2 decision),
+  P[(u - 1) & 1]  P~ of tile u-1, waiting for its P~V product,
+  LDS             K_hat(u+1) and V(u-1) have been requested NST-1 iterations ago.
+Iteration u: wait for own copies, barrier, request K_hat(u+NST) and V(u+NST-2) (as far as the list
+goes: cntk tiles can be copied as whole blocks, cnt tiles exist); then one "step":
+  vector ALU: softmax of tile u  ->  P[u & 1], row sum
+  MFMA:       scores of tile u+1 -> S[(u + 1) & 1];  O += P~(u-1) V(u-1)
+as a sequence of slots: operand read (LDS, three slots ahead), one MFMA, a chunk of the softmax.
+The row maximum of the fresh scores, the stage-2 test (Alg. 1 line 15) and the test whether the
+reference maximum must move follow at the end of the step; the block leaves when one of them says so.
 """
 import os
 
@@ -29,7 +32,8 @@ MAGIC_NEG = 0xCB400000  # bit pattern of -12582912.0f = -(1.5 * 2^23)
 RESCALE_T = 0x41000000  # 8.0f
 LA = 3                  # operand reads run this many slots ahead
 RING = LA + 1
-PRE_UNITS = 14          # vector work placed before the first MFMA of a step (covers the LDS latency)
+PRE_UNITS = 10          # vector work placed before the first MFMA of a step (covers the LDS latency)
+NWAVE = 4               # waves per workgroup sharing the tile copies
 
 
 class Cfg:
@@ -39,85 +43,76 @@ class Cfg:
         self.NQK, self.NPV = 2 * self.NSTEP, 4 * self.NDT
         self.NSLOT = self.NQK + self.NPV
         self.K_BYTES, self.V_BYTES = 64 * D, D * 128
-        self.KD, self.VD = self.K_BYTES // 2048, self.V_BYTES // 2048  # copies per wave and tile
+        self.KD, self.VD = self.K_BYTES // (1024 * NWAVE), self.V_BYTES // (1024 * NWAVE)  # copies per wave
         self.NDMA = self.KD + self.VD
-        # ---- AGPRs ----
-        self.AO, self.BO = 0, 16 * self.NDT
-        self.AQ = 32 * self.NDT
-        self.BQ = self.AQ + 4 * self.NSTEP
-        # ---- VGPRs (pinned) ----
-        self.BS, self.AS, self.AP, self.BP, self.MG, self.RG = 32, 64, 96, 112, 128, 144
-        (self.A_MT, self.A_MR, self.A_L, self.B_MT, self.B_MR, self.B_L, self.A_INV, self.B_INV) = range(160, 168)
-        self.KOFF, self.KA, self.VOFF, self.VA = 168, 172, 176, 180
-        self.KSRC, self.VSRC = 184, 188
-        self.T = 196          # 8 temporaries
-        self.CX, self.MLOC, self.L0, self.L1 = 204, 205, 206, 207
+        # ---- VGPRs (pinned; the kernel uses no AGPRs, so all 256 registers of a wave are VGPRs) ----
+        self.S = (0, 32)
+        self.P = (64, 80)
+        self.MG, self.RG = 96, 112
+        (self.MT, self.MR, self.L, self.INV, self.CX) = range(128, 133)
+        self.T = 133                              # 3 temporaries
+        self.L0, self.L1, self.L2 = 133, 134, 135  # list prefetch: read back before the temporaries are used
+        self.MLOC = 135
+        self.KA, self.VA = 136, 140   # per-lane LDS addresses of the operand reads in buffer 0
+        self.KSRC, self.VSRC = 144, 145
+        self.O = 146
+        self.Q = self.O + 16 * self.NDT
+        self.NVGPR = self.Q + 4 * self.NSTEP
         # ---- SGPRs (pinned) ----
-        names = ("u uend kb0 kb1 vb0 vb1 ldsk ldskd ldsv ldsvd ldsjl ldsscl lam2 execA execB pvA pvB scB "
-                 "jk jv scn bk negmagic rt jkn scnn t0 t1 t2 t3 kcur vcur dk dv a0 a1").split()
-        self.S = {n: 36 + i for i, n in enumerate(names)}
-
-
-class Group:
-    def __init__(self, c, which):
-        a = which == "A"
-        self.S, self.P = (c.AS, c.AP) if a else (c.BS, c.BP)
-        self.O, self.Q = (c.AO, c.AQ) if a else (c.BO, c.BQ)
-        self.mt, self.mr, self.l, self.inv = (c.A_MT, c.A_MR, c.A_L, c.A_INV) if a else (c.B_MT, c.B_MR, c.B_L, c.B_INV)
-        self.pv = c.S["pvA" if a else "pvB"]
-        self.ex = c.S["execA" if a else "execB"]
-        self.name = which
+        names = ("u uend kb0 kb1 vb0 vb1 ldskd ldsvd ldsjl ldsscl lam2 exec need pv scx scn "
+                 "jk jv r negmagic rt scnn t0 t1 a0 a1 cnt cntk").split()
+        self.sg = {n: 36 + i for i, n in enumerate(names)}
+        assert self.sg["kb0"] % 2 == 0 and self.sg["vb0"] % 2 == 0 and self.sg["a0"] % 2 == 0, self.sg
 
 
 def vr(b, n=1):
     return f"v{b}" if n == 1 else f"v[{b}:{b + n - 1}]"
 
 
-def ar(b, n=1):
-    return f"a{b}" if n == 1 else f"a[{b}:{b + n - 1}]"
-
-
-def gen_step(c, o, X, Y, scx, lbl, prefetch):
-    """Softmax of X's pending scores | scores of Y's next tile and Y's pending P~V; then Y's row maximum."""
-    s = c.S
+def gen_step(c, o, cur, NST, kbuf, vbuf):
+    """One iteration body: softmax of S[cur] -> P[cur]; scores of the next tile -> S[1-cur];
+    O += P[1-cur] V; then the row maximum of the fresh scores and the two decisions."""
+    s = c.sg
+    nxt = 1 - cur
+    XS, XP, YS, YP = c.S[cur], c.P[cur], c.S[nxt], c.P[nxt]
     T0, T1, T2 = c.T, c.T + 1, c.T + 2
 
     def read(sl):
         dst = c.RG + 4 * (sl % RING)
         if sl < c.NQK:
             kh, st = sl % 2, sl // 2
-            o(f"ds_read_b128 {vr(dst, 4)}, v{c.KA + st} offset:{kh * 32 * c.D}")
+            o(f"ds_read_b128 {vr(dst, 4)}, v{c.KA + st} offset:{kbuf * c.K_BYTES + kh * 32 * c.D}")
         else:
             ks, dt = divmod(sl - c.NQK, c.NDT)
-            o(f"ds_read_b128 {vr(dst, 4)}, v{c.VA + ks} offset:{dt * 4096}")
+            o(f"ds_read_b128 {vr(dst, 4)}, v{c.VA + ks} offset:{vbuf * c.V_BYTES + dt * 4096}")
 
     def mfma(sl):
         src = c.RG + 4 * (sl % RING)
         if sl < c.NQK:
             kh, st = sl % 2, sl // 2
-            d = Y.S + 16 * kh
+            d = YS + 16 * kh
             acc = vr(c.MG, 16) if st == 0 else vr(d, 16)
-            o(f"v_mfma_i32_32x32x32_i8 {vr(d, 16)}, {vr(src, 4)}, {ar(Y.Q + 4 * st, 4)}, {acc}")
+            o(f"v_mfma_i32_32x32x32_i8 {vr(d, 16)}, {vr(src, 4)}, {vr(c.Q + 4 * st, 4)}, {acc}")
         else:
             ks, dt = divmod(sl - c.NQK, c.NDT)
-            a = Y.O + 16 * dt
-            o(f"v_mfma_f32_32x32x16_{c.dt} {ar(a, 16)}, {vr(src, 4)}, {vr(Y.P + 4 * ks, 4)}, {ar(a, 16)}")
+            a = c.O + 16 * dt
+            o(f"v_mfma_f32_32x32x16_{c.dt} {vr(a, 16)}, {vr(src, 4)}, {vr(YP + 4 * ks, 4)}, {vr(a, 16)}")
 
     # ---- the vector instruction stream of the step: (text, issue units) ----
     ops = []
-    x = lambda e: X.S + e
-    F = lambda e: ops.append((f"v_fma_f32 v{x(e)}, v{x(e)}, s{scx}, v{c.CX}", 1))
+    x = lambda e: XS + e
+    F = lambda e: ops.append((f"v_fma_f32 v{x(e)}, v{x(e)}, s{s['scx']}, v{c.CX}", 1))
     E = lambda e: ops.append((f"v_exp_f32 v{x(e)}, v{x(e)}", 2))
-    A = lambda e: ops.append((f"v_add_f32 v{X.l}, v{X.l}, v{x(e)}", 1))
-    C = lambda w: ops.append((f"v_cvt_pk_{c.dt}_f32 v{X.P + w}, v{x(2 * w)}, v{x(2 * w + 1)}", 1))
+    A = lambda e: ops.append((f"v_add_f32 v{c.L}, v{c.L}, v{x(e)}", 1))
+    C = lambda w: ops.append((f"v_cvt_pk_{c.dt}_f32 v{XP + w}, v{x(2 * w)}, v{x(2 * w + 1)}", 1))
     for k in range(16):
         F(2 * k); F(2 * k + 1); E(2 * k); E(2 * k + 1)
         if k:
             A(2 * k - 2); A(2 * k - 1); C(k - 1)
     A(30); A(31); C(15)
-    n_exp_ops = len(ops)
-    # row maximum of Y's fresh scores (biased integers compare like the scores themselves)
-    y = lambda e: Y.S + e
+    first_max = len(ops)  # index of the first instruction that reads the fresh scores
+    # row maximum of the fresh scores (biased integers compare like the scores themselves)
+    y = lambda e: YS + e
     chains = []
     for t, base in ((T0, y(0)), (T1, y(16))):
         ch = [f"v_max3_i32 v{t}, v{base}, v{base + 1}, v{base + 2}"]
@@ -126,227 +121,208 @@ def gen_step(c, o, X, Y, scx, lbl, prefetch):
         chains.append(ch)
     for a_, b_ in zip(*chains):
         ops.append((a_, 1)); ops.append((b_, 1))
-    ops += [(f"v_max_i32 v{T0}, v{T0}, v{T1}", 1),
-            (f"v_add_f32 v{T0}, s{s['negmagic']}, v{T0}", 1),      # biased integer (as float) -> score sum
-            (f"v_mul_f32 v{T0}, s{s['scn']}, v{T0}", 1),           # -> log2-domain score
-            (f"v_mov_b32 v{T1}, v{T0}", 1),
-            ("s_nop 1", 1),
-            (f"v_permlane32_swap_b32 v{T0}, v{T1}", 1),            # exchange with the lane holding the other 16 keys
-            ("s_nop 1", 1),
-            (f"v_max_f32 v{c.MLOC}, v{T0}, v{T1}", 1),
-            (f"v_max_f32 v{Y.mt}, v{Y.mt}, v{c.MLOC}", 1),         # new running maximum
-            (f"v_sub_f32 v{T0}, v{c.MLOC}, v{Y.mt}", 1),
-            (f"v_sub_f32 v{T1}, v{Y.mt}, v{Y.mr}", 1),
-            (f"v_add_f32 v{T0}, v{T0}, v{Y.inv}", 1),              # rows past N: -inf
-            (f"v_add_f32 v{T1}, v{T1}, v{Y.inv}", 1)]
-    first_max = n_exp_ops  # index of the first instruction that reads Y's fresh scores
-    NTAIL = 13             # the dependent chain at the end stays behind the last MFMA
+    tail = [f"v_max_i32 v{T0}, v{T0}, v{T1}",
+            f"v_add_f32 v{T0}, s{s['negmagic']}, v{T0}",      # biased integer (as float) -> integer score
+            f"v_mul_f32 v{T0}, s{s['scn']}, v{T0}",           # -> log2-domain score
+            f"v_mov_b32 v{T1}, v{T0}",
+            "s_nop 1",
+            f"v_permlane32_swap_b32 v{T0}, v{T1}",            # exchange with the lane holding the other 16 keys
+            "s_nop 1",
+            f"v_max_f32 v{c.MLOC}, v{T0}, v{T1}",
+            f"v_max_f32 v{c.MT}, v{c.MT}, v{c.MLOC}",         # new running maximum
+            f"v_sub_f32 v{T0}, v{c.MLOC}, v{c.MT}",
+            f"v_sub_f32 v{T1}, v{c.MT}, v{c.MR}",
+            f"v_add_f32 v{T0}, v{T0}, v{c.INV}",              # rows past N: -inf
+            f"v_add_f32 v{T1}, v{T1}, v{c.INV}"]
 
-    body = ops[:-NTAIL]
-    total = sum(u for _, u in body)
+    total = sum(u for _, u in ops)
     per_slot = (total - PRE_UNITS) / c.NSLOT
     # chunk 0 runs before the first MFMA, chunk sl + 1 after MFMA sl
     chunks, acc_u, idx = [], 0.0, 0
     for k in range(c.NSLOT + 1):
         target = PRE_UNITS + per_slot * k
         ch = []
-        while idx < len(body) and (acc_u + body[idx][1] / 2 <= target or k == c.NSLOT):
-            ch.append(idx); acc_u += body[idx][1]; idx += 1
+        while idx < len(ops) and (acc_u + ops[idx][1] / 2 <= target or k == c.NSLOT):
+            if idx == first_max:
+                # the fresh scores are complete a few slots after the last Q K^T MFMA
+                assert k - 1 >= c.NQK + 1, "row-maximum work scheduled too early"
+            ch.append(ops[idx][0]); acc_u += ops[idx][1]
+            idx += 1
         chunks.append(ch)
-    chunks[-1] += list(range(len(body), len(ops)))
-    # the scores of Y are complete a few slots after the last Q K^T MFMA
-    for k, ch in enumerate(chunks):
-        if any(i >= first_max for i in ch):
-            assert k - 1 >= c.NQK + 1, "row-maximum work scheduled too early"
-            break
+    chunks[-1] += tail
     assert len(chunks[-1]) >= 12, "too little vector work behind the last MFMA"
 
-    o(f"; ---- {lbl}: softmax of group {X.name} | MFMAs for group {Y.name}")
-    if prefetch:  # list entries of the next iteration (older than every operand read of this step)
-        o(f"s_add_u32 s{s['t0']}, s{s['u']}, {prefetch}")
-        o(f"s_lshl_b32 s{s['t0']}, s{s['t0']}, 1")
-        o(f"s_add_u32 s{s['t0']}, s{s['t0']}, s{s['ldsjl']}")
-        o(f"s_lshl_b32 s{s['t1']}, s{s['u']}, 2")
-        o(f"s_add_u32 s{s['t1']}, s{s['t1']}, s{s['ldsscl']}")
-        o(f"v_mov_b32 v{c.L0}, s{s['t0']}")
-        o(f"v_mov_b32 v{c.L1}, s{s['t1']}")
-        o(f"ds_read_u16 v{c.L0}, v{c.L0}")
-        o(f"ds_read_b32 v{c.L1}, v{c.L1} offset:4")
+    o(f"; ---- step: softmax S{cur} -> P{cur} | scores -> S{nxt}, O += P{nxt} V")
+    # list entries the next iteration needs (older than every operand read of this step)
+    o(f"s_lshl_b32 s{s['t0']}, s{s['u']}, 1")
+    o(f"s_add_u32 s{s['t0']}, s{s['t0']}, s{s['ldsjl']}")
+    o(f"s_lshl_b32 s{s['t1']}, s{s['u']}, 2")
+    o(f"s_add_u32 s{s['t1']}, s{s['t1']}, s{s['ldsscl']}")
+    o(f"v_mov_b32 v{c.L0}, s{s['t0']}")
+    o(f"v_mov_b32 v{c.L2}, s{s['t1']}")
+    o(f"ds_read_u16 v{c.L1}, v{c.L0} offset:{2 * (NST - 1)}")   # key block of V(u+1+NST-2)
+    o(f"ds_read_u16 v{c.L0}, v{c.L0} offset:{2 * (NST + 1)}")   # key block of K_hat(u+1+NST)
+    o(f"ds_read_b32 v{c.L2}, v{c.L2} offset:8")                 # scale of tile u+2
     for sl in range(LA):
         read(sl)
-    o(f"v_mov_b32 v{T2}, s{s['negmagic']}")
-    o(f"v_fma_f32 v{c.CX}, v{T2}, s{scx}, -v{X.mr}")   # -(bias * scale) - reference maximum
-    o(f"s_add_u32 s{Y.pv}, s{Y.pv}, 1")
-    for i in chunks[0]:
-        o(ops[i][0])
+    o(f"v_mov_b32 v{c.CX}, s{s['negmagic']}")
+    o(f"v_fma_f32 v{c.CX}, v{c.CX}, s{s['scx']}, -v{c.MR}")   # -(bias * scale) - reference maximum
+    o(f"s_add_u32 s{s['pv']}, s{s['pv']}, 1")
+    for t in chunks[0]:
+        o(t)
     for sl in range(c.NSLOT):
         if sl + LA < c.NSLOT:
             read(sl + LA)
         o(f"s_waitcnt lgkmcnt({min(LA, c.NSLOT - 1 - sl)})")
         mfma(sl)
-        for i in chunks[sl + 1]:
-            o(ops[i][0])
-    # stage-2 decision of Y's new tile and "has the maximum run away from the reference"
+        if sl == 0:  # the list entries (older than the operand reads) have arrived
+            o(f"v_readfirstlane_b32 s{s['jk']}, v{c.L0}")
+            o(f"v_readfirstlane_b32 s{s['jv']}, v{c.L1}")
+            o(f"v_readfirstlane_b32 s{s['scnn']}, v{c.L2}")
+        for t in chunks[sl + 1]:
+            o(t)
+    # stage-2 decision of the new tile; has the maximum run away from the reference?
     o(f"v_cmp_lt_f32 vcc, s{s['lam2']}, v{T0}")
-    o(f"s_cmp_lg_u64 vcc, 0")
-    o(f"s_cselect_b32 s{Y.ex}, 1, 0")
-    if prefetch:
-        o(f"v_readfirstlane_b32 s{s['jkn']}, v{c.L0}")
-        o(f"v_readfirstlane_b32 s{s['scnn']}, v{c.L1}")
+    o("s_cmp_lg_u64 vcc, 0")
+    o(f"s_cselect_b32 s{s['exec']}, 1, 0")
     o(f"v_cmp_lt_f32 vcc, s{s['rt']}, v{T1}")
-    o(f"s_cbranch_vccnz L_rescale{Y.name}_%=")
-    o(f"L_after{Y.name}_%=:")
+    o("s_cmp_lg_u64 vcc, 0")
+    o(f"s_cselect_b32 s{s['need']}, 1, 0")
+    o(f"s_add_u32 s{s['u']}, s{s['u']}, 1")
+    o(f"s_mov_b32 s{s['scx']}, s{s['scn']}")
+    o(f"s_mov_b32 s{s['scn']}, s{s['scnn']}")
 
 
-def gen_rescale(c, o, G, cont):
-    """Move the reference maximum of group G up to its running maximum: O, l *= 2^(m_ref - m)."""
-    T = c.T
-    F = c.T + 7
-    o(f"L_rescale{G.name}_%=:")
-    o("s_nop 7"); o("s_nop 7"); o("s_nop 7")   # the group's last MFMA results have landed
-    o(f"v_sub_f32 v{F}, v{G.mr}, v{G.mt}")
-    o(f"v_exp_f32 v{F}, v{F}")
-    o("s_nop 1")
-    n = 16 * c.NDT
-    for i0 in range(0, n, 4):
-        for j in range(4):
-            o(f"v_accvgpr_read_b32 v{T + j}, a{G.O + i0 + j}")
-        for j in range(4):
-            o(f"v_mul_f32 v{T + j}, v{T + j}, v{F}")
-        for j in range(4):
-            o(f"v_accvgpr_write_b32 a{G.O + i0 + j}, v{T + j}")
-    o(f"v_mul_f32 v{G.l}, v{G.l}, v{F}")
-    o(f"v_mov_b32 v{G.mr}, v{G.mt}")
-    o("s_nop 3")
-    o(f"s_branch {cont}")
-
-
-def gen_loop(c, NST):
-    s = c.S
-    lines = []
-    o = lines.append
-    A, B = Group(c, "A"), Group(c, "B")
-    wait = c.NDMA * (NST - 2)
-
-    def mod_nst(dst, src, add):
-        o(f"s_add_u32 s{dst}, s{src}, {add}")
-        o(f"s_cmp_ge_u32 s{dst}, {NST}")
-        o(f"s_cselect_b32 s{s['t3']}, {NST}, 0")
-        o(f"s_sub_u32 s{dst}, s{dst}, s{s['t3']}")
-
-    o(f"s_mov_b32 s{s['negmagic']}, 0x{MAGIC_NEG:08x}")
-    o(f"s_mov_b32 s{s['rt']}, 0x{RESCALE_T:08x}")
-    o("s_waitcnt vmcnt(0) lgkmcnt(0)")
-    o("s_branch L_check_%=")
-    o("L_top_%=:")
-    o(f"s_waitcnt vmcnt({wait})")
+def gen_top(c, o, NST, dkbuf, dvbuf, r, late):
+    """Top of an iteration: wait, barrier, the wave's share of the next tile copies.  Copies are issued
+    in groups {K_hat(t+1), V(t-1)}, group u+NST-1 here; near the end of the list a group shrinks."""
+    s = c.sg
+    if NST == 3:
+        # younger than the group this iteration needs: group u+1 = {K_hat(u+2), V(u)}
+        o(f"s_add_u32 s{s['t0']}, s{s['u']}, 2")
+        o(f"s_cmp_lt_u32 s{s['t0']}, s{s['cntk']}")
+        o(f"s_cbranch_scc0 L_tailw{r}_%=")
+        o(f"s_waitcnt vmcnt({c.NDMA})")
+        o(f"L_waited{r}_%=:")
+        late.append((f"L_tailw{r}_%=", [f"s_waitcnt vmcnt({c.VD})", f"s_branch L_waited{r}_%="]))
+    else:
+        assert NST == 2
+        o("s_waitcnt vmcnt(0)")
     o("s_barrier")
-    # ---- buffers of this iteration: K_hat(u) in bk, V(u-1) in bk-1; copies go to bk-1 (K) and bk-2 (V)
-    mod_nst(s['t0'], s['bk'], NST - 1)
-    mod_nst(s['t1'], s['bk'], NST - 2 if NST > 2 else 0)
-    o(f"s_mul_i32 s{s['kcur']}, s{s['bk']}, {c.K_BYTES}")
-    o(f"s_add_u32 s{s['kcur']}, s{s['kcur']}, s{s['ldsk']}")
-    o(f"s_mul_i32 s{s['vcur']}, s{s['t0']}, {c.V_BYTES}")
-    o(f"s_add_u32 s{s['vcur']}, s{s['vcur']}, s{s['ldsv']}")
-    o(f"s_mul_i32 s{s['dk']}, s{s['t0']}, {c.K_BYTES}")
-    o(f"s_add_u32 s{s['dk']}, s{s['dk']}, s{s['ldskd']}")
-    o(f"s_mul_i32 s{s['dv']}, s{s['t1']}, {c.V_BYTES}")
-    o(f"s_add_u32 s{s['dv']}, s{s['dv']}, s{s['ldsvd']}")
-    # ---- LDS-DMA: this wave's pieces of K_hat(jk) and V(jv)
+    # LDS-DMA: this wave's pieces of K_hat(jk) and V(jv)
+    o(f"s_add_u32 s{s['t0']}, s{s['u']}, {NST}")
+    o(f"s_cmp_lt_u32 s{s['t0']}, s{s['cntk']}")
+    o(f"s_cbranch_scc0 L_skipk{r}_%=")
     o(f"s_mul_i32 s{s['t0']}, s{s['jk']}, {c.K_BYTES}")
     o(f"s_add_u32 s{s['a0']}, s{s['kb0']}, s{s['t0']}")
     o(f"s_addc_u32 s{s['a1']}, s{s['kb1']}, 0")
     for n in range(c.KD):
-        o(f"s_add_u32 m0, s{s['dk']}, {n * 2048}")
+        if n:  # the wave's next piece lies 4 KB further on both sides
+            o(f"s_add_u32 s{s['a0']}, s{s['a0']}, {1024 * NWAVE}")
+            o(f"s_addc_u32 s{s['a1']}, s{s['a1']}, 0")
+        o(f"s_add_u32 m0, s{s['ldskd']}, {dkbuf * c.K_BYTES + n * 1024 * NWAVE}")
         o("s_nop 0")
-        o(f"global_load_lds_dwordx4 v{c.KSRC + n}, s[{s['a0']}:{s['a1']}]")
+        o(f"global_load_lds_dwordx4 v{c.KSRC}, s[{s['a0']}:{s['a1']}]")
+    o(f"L_skipk{r}_%=:")
+    o(f"s_add_u32 s{s['t0']}, s{s['u']}, {NST - 2}")
+    o(f"s_cmp_lt_u32 s{s['t0']}, s{s['cnt']}")
+    o(f"s_cbranch_scc0 L_skipv{r}_%=")
     o(f"s_mul_i32 s{s['t0']}, s{s['jv']}, {c.V_BYTES}")
     o(f"s_add_u32 s{s['a0']}, s{s['vb0']}, s{s['t0']}")
     o(f"s_addc_u32 s{s['a1']}, s{s['vb1']}, 0")
     for n in range(c.VD):
-        o(f"s_add_u32 m0, s{s['dv']}, {n * 2048}")
+        if n:
+            o(f"s_add_u32 s{s['a0']}, s{s['a0']}, {1024 * NWAVE}")
+            o(f"s_addc_u32 s{s['a1']}, s{s['a1']}, 0")
+        o(f"s_add_u32 m0, s{s['ldsvd']}, {dvbuf * c.V_BYTES + n * 1024 * NWAVE}")
         o("s_nop 0")
-        o(f"global_load_lds_dwordx4 v{c.VSRC + n}, s[{s['a0']}:{s['a1']}]")
-    # ---- operand addresses of this iteration
-    for st in range(c.NSTEP):
-        o(f"v_add_u32 v{c.KA + st}, s{s['kcur']}, v{c.KOFF + st}")
-    for ks in range(4):
-        o(f"v_add_u32 v{c.VA + ks}, s{s['vcur']}, v{c.VOFF + ks}")
-    gen_step(c, o, B, A, s['scB'], "step 1", 0)
-    gen_step(c, o, A, B, s['scn'], "step 2", NST)
-    # ---- next iteration
-    o(f"s_add_u32 s{s['u']}, s{s['u']}, 1")
-    o(f"s_mov_b32 s{s['scB']}, s{s['scn']}")
-    o(f"s_mov_b32 s{s['scn']}, s{s['scnn']}")
-    o(f"s_mov_b32 s{s['jv']}, s{s['jk']}")
-    o(f"s_mov_b32 s{s['jk']}, s{s['jkn']}")
-    mod_nst(s['bk'], s['bk'], 1)
-    o("L_check_%=:")
+        o(f"global_load_lds_dwordx4 v{c.VSRC}, s[{s['a0']}:{s['a1']}]")
+    o(f"L_skipv{r}_%=:")
+
+
+def gen_check(c, o, go):
+    s = c.sg
     o(f"s_cmp_ge_u32 s{s['u']}, s{s['uend']}")
     o("s_cbranch_scc1 L_exit_%=")
-    o(f"s_and_b32 s{s['t0']}, s{s['execA']}, s{s['execB']}")
-    o(f"s_cmp_eq_u32 s{s['t0']}, 0")
-    o("s_cbranch_scc0 L_top_%=")
+    o(f"s_cmp_eq_u32 s{s['exec']}, 0")
+    o("s_cbranch_scc1 L_exit_%=")
+    o(f"s_cmp_eq_u32 s{s['need']}, 0")
+    o(f"s_cbranch_scc1 {go}")
     o("s_branch L_exit_%=")
-    gen_rescale(c, o, A, "L_afterA_%=")
-    gen_rescale(c, o, B, "L_afterB_%=")
+
+
+def gen_loop(c, NST):
+    s = c.sg
+    lines = []
+    o = lines.append
+    period = 2 * NST if NST % 2 else NST  # bodies: one per value of u mod lcm(2, NST)
+    o(f"s_mov_b32 s{s['negmagic']}, 0x{MAGIC_NEG:08x}")
+    o(f"s_mov_b32 s{s['rt']}, 0x{RESCALE_T:08x}")
+    o("s_waitcnt vmcnt(0) lgkmcnt(0)")
+    for r in range(1, period):
+        o(f"s_cmp_eq_u32 s{s['r']}, {r}")
+        o(f"s_cbranch_scc1 L_body{r}_%=")
+    late = []  # out-of-line pieces: (label, instructions)
+    for r in range(period):
+        o(f"L_body{r}_%=:")
+        # iteration u = r (mod period): K_hat(u+1) in buffer (u+1) % NST, V(u-1) in (u-1) % NST;
+        # the new copies go to u % NST (K_hat) and (u-2) % NST (V)
+        gen_top(c, o, NST, r % NST, (r - 2) % NST, r, late)
+        gen_step(c, o, r & 1, NST, (r + 1) % NST, (r - 1) % NST)
+        gen_check(c, o, f"L_body{(r + 1) % period}_%=")
+    for label, ins in late:
+        o(label + ":")
+        for i in ins:
+            o(i)
     o("L_exit_%=:")
-    o("s_nop 7"); o("s_nop 7"); o("s_nop 7")
+    o("s_nop 7"); o("s_nop 7"); o("s_nop 7")   # the last MFMA results have landed
     return lines
 
 
 def clobbers(c):
-    v = list(range(c.AS, c.AS + 32)) + list(range(c.BP, c.BP + 16)) + list(range(c.RG, c.RG + 16))
-    v += list(range(c.KA, c.KA + 4)) + list(range(c.VA, c.VA + 4)) + list(range(c.T, c.T + 8))
-    v += [c.CX, c.MLOC, c.L0, c.L1]
-    sg = [c.S[n] for n in "negmagic rt jkn scnn t0 t1 t2 t3 kcur vcur dk dv a0 a1".split()]
+    v = list(range(c.RG, c.RG + 16)) + list(range(c.T, c.T + 3)) + [c.CX]
+    sg = [c.sg[n] for n in "negmagic rt scnn t0 t1 a0 a1".split()]
     return [f"v{i}" for i in v] + [f"s{i}" for i in sg] + ["vcc", "scc", "memory"]
 
 
 def gen_function(c, NST):
-    s = c.S
+    s = c.sg
     body = gen_loop(c, NST)
     dtn = "SPARGE_BF16" if c.dt == "bf16" else "SPARGE_F16"
     out = []
     w = out.append
-    w(f"// head dimension {c.D}, {c.dt}, {NST} LDS stages")
+    w(f"// head dimension {c.D}, {c.dt}, {NST} LDS stages: {c.NVGPR} VGPRs pinned, no AGPRs")
     w(f"template <> struct FastLoop<{c.D}, {dtn}, {NST}> {{")
-    w("    template <class Grp>")
-    w("    static __device__ __forceinline__ void run(Grp& A, Grp& B, const v16i& magic, FastLoopArgs& p) {")
+    w("    template <class St>")
+    w("    static __device__ __forceinline__ void run(St& w, const v16i& magic, FastLoopArgs& p) {")
     w("        asm volatile(")
     for l in body:
         w(f'            "{l}\\n"')
-    # operands
     outs, ins = [], []
     for dt in range(c.NDT):
-        outs.append(f'"+{{{ar(c.AO + 16 * dt, 16)}}}"(A.O[{dt}])')
-        outs.append(f'"+{{{ar(c.BO + 16 * dt, 16)}}}"(B.O[{dt}])')
-    for kh in range(2):
-        outs.append(f'"+{{{vr(c.BS + 16 * kh, 16)}}}"(B.S[{kh}])')
-    for ks in range(4):
-        outs.append(f'"+{{{vr(c.AP + 4 * ks, 4)}}}"(A.P[{ks}])')
-    for reg, expr in ((c.A_MT, "A.m_true"), (c.A_MR, "A.m_ref"), (c.A_L, "A.l"), (c.B_MT, "B.m_true"),
-                      (c.B_MR, "B.m_ref"), (c.B_L, "B.l")):
+        outs.append(f'"+{{{vr(c.O + 16 * dt, 16)}}}"(w.O[{dt}])')
+    for b in range(2):
+        for kh in range(2):
+            outs.append(f'"+{{{vr(c.S[b] + 16 * kh, 16)}}}"(w.S[{b}][{kh}])')
+        for ks in range(4):
+            outs.append(f'"+{{{vr(c.P[b] + 4 * ks, 4)}}}"(w.P[{b}][{ks}])')
+    for reg, expr in ((c.MT, "w.m_true"), (c.MR, "w.m_ref"), (c.L, "w.l")):
         outs.append(f'"+{{v{reg}}}"({expr})')
-    for n in "u bk jk jv scn scB execA execB pvA pvB".split():
+    for n in "u jk jv scn scx exec need pv".split():
         outs.append(f'"+{{s{s[n]}}}"(p.{n})')
     for st in range(c.NSTEP):
-        ins.append(f'"{{{ar(c.AQ + 4 * st, 4)}}}"(A.qf[{st}])')
-        ins.append(f'"{{{ar(c.BQ + 4 * st, 4)}}}"(B.qf[{st}])')
+        ins.append(f'"{{{vr(c.Q + 4 * st, 4)}}}"(w.qf[{st}])')
     ins.append(f'"{{{vr(c.MG, 16)}}}"(magic)')
-    ins.append(f'"{{v{c.A_INV}}}"(p.invalA)')
-    ins.append(f'"{{v{c.B_INV}}}"(p.invalB)')
+    ins.append(f'"{{v{c.INV}}}"(p.inval)')
     for st in range(c.NSTEP):
-        ins.append(f'"{{v{c.KOFF + st}}}"(p.k_off[{st}])')
+        ins.append(f'"{{v{c.KA + st}}}"(p.k_adr[{st}])')
     for ks in range(4):
-        ins.append(f'"{{v{c.VOFF + ks}}}"(p.v_off[{ks}])')
-    for n in range(c.KD):
-        ins.append(f'"{{v{c.KSRC + n}}}"(p.k_src[{n}])')
-    for n in range(c.VD):
-        ins.append(f'"{{v{c.VSRC + n}}}"(p.v_src[{n}])')
+        ins.append(f'"{{v{c.VA + ks}}}"(p.v_adr[{ks}])')
+    ins.append(f'"{{v{c.KSRC}}}"(p.k_src)')
+    ins.append(f'"{{v{c.VSRC}}}"(p.v_src)')
     ins.append(f'"{{s[{s["kb0"]}:{s["kb1"]}]}}"(p.kbase)')
     ins.append(f'"{{s[{s["vb0"]}:{s["vb1"]}]}}"(p.vbase)')
-    for n in "uend ldsk ldskd ldsv ldsvd ldsjl ldsscl lam2".split():
+    for n in "r uend cnt cntk ldskd ldsvd ldsjl ldsscl lam2".split():
         ins.append(f'"{{s{s[n]}}}"(p.{n})')
     w("            : " + ",\n              ".join(outs))
     w("            : " + ",\n              ".join(ins))

@@ -5,6 +5,12 @@ from synth import make_workload
 from synth.workloads import Workload
 
 
+# How far a row's maximum may run ahead of the value the kernel subtracts inside exp (natural-log
+# units; SPARGE_REF_SLACK_LOG2 of sparge.h): the oracle's loop takes it as ref_slack so that P~ is
+# rounded to 16 bits at the same point on both sides.
+REF_SLACK = 8 * float(np.log(2.0))
+
+
 def f32(x) -> float:
     """The value a host float array hands to the library."""
     return float(np.float32(x))

@@ -509,3 +509,68 @@ def test_judge_matters_on_non_self_similar_blocks():
     with_j, _ = so.spargeattn(Q, K, V, tau=0.6, theta=0.5, lam=-np.inf, quant=False)
     no_j, _ = so.spargeattn(Q, K, V, tau=0.6, theta=-np.inf, lam=-np.inf, quant=False)
     assert so.rel_l1(with_j.O, ref) < so.rel_l1(no_j.O, ref)
+
+
+# ---------------------------------------------------------------------------------------------
+# The reference maximum inside exp is free (rescaling identity of Sec. 3.1)
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("causal", [False, True])
+def test_reference_slack_does_not_change_the_result_without_rounding(causal):
+    """O/l does not depend on the reference that exp subtracts: any slack gives the same output up to
+    fp64 rounding, the same executed groups and the same counters (the stage-2 test uses the true m)."""
+    rng = np.random.default_rng(31)
+    N, d = 333, 16
+    Q, K, V = 3.0 * rng.standard_normal((N, d)), rng.standard_normal((N, d)), rng.standard_normal((N, d))
+    mask = rng.random((so.nblocks(N, so.BQ), so.nblocks(N, so.BK))) < 0.7
+    mask[:, 0] = True
+    if causal:
+        mask[np.arange(mask.shape[0]), 2 * np.arange(mask.shape[0])] = True
+    base = so.sparse_attention(Q, K, V, mask, lam=-3.0, causal=causal, quant=True, pv_dtype="none")
+    for slack in (0.5, 8 * math.log(2.0), 1e9):
+        r = so.sparse_attention(Q, K, V, mask, lam=-3.0, causal=causal, quant=True, pv_dtype="none", ref_slack=slack)
+        assert np.abs(r.O - base.O).max() < 1e-12
+        assert (r.qk_tiles, r.pv_groups, r.valid_tiles, r.valid_groups) == \
+            (base.qk_tiles, base.pv_groups, base.valid_tiles, base.valid_groups)
+    dense = so.dense_attention(*so.dequantized_qk(Q, K), V, causal=causal, block_mask=mask)
+    nolam = so.sparse_attention(Q, K, V, mask, causal=causal, quant=True, pv_dtype="none", ref_slack=8 * math.log(2.0))
+    assert np.abs(nolam.O - dense).max() < 1e-10
+
+
+def test_reference_slack_only_moves_the_16_bit_rounding_of_p():
+    """With P~ rounded to 16 bits the slack changes the result by rounding noise only, and P~ stays
+    below exp(slack) (it is at most 1 with slack 0)."""
+    rng = np.random.default_rng(32)
+    N, d = 400, 32
+    Q, K, V = 2.0 * rng.standard_normal((N, d)), rng.standard_normal((N, d)), rng.standard_normal((N, d))
+    exact = so.sparse_attention(Q, K, V, None, quant=True, pv_dtype="none")
+    for dt, tol in (("fp16", 2e-3), ("bf16", 1.2e-2)):
+        a = so.sparse_attention(Q, K, V, None, quant=True, pv_dtype=dt)
+        b = so.sparse_attention(Q, K, V, None, quant=True, pv_dtype=dt, ref_slack=8 * math.log(2.0))
+        assert so.rel_l1(a.O, exact.O) < tol and so.rel_l1(b.O, exact.O) < tol
+        assert 0 < so.rel_l1(b.O, a.O) < tol
+
+
+def test_reference_moves_per_row_group_when_one_row_runs_ahead():
+    """Two tiles, one row of the first 32-row group gets a much larger score in the second tile:
+    with slack s that group's reference moves (its P~ are again <= 1), the other groups keep theirs.
+    Checked through the rounding: V = e_0, P~ rounded to bf16, compare with a direct evaluation."""
+    N, d = 128, 8
+    Q = np.zeros((N, d)); K = np.zeros((N, d)); V = np.zeros((N, d))
+    Q[:, 0] = 1.0
+    K[:64, 0] = 1.0                      # tile 0: every score equal
+    K[64:, 0] = np.linspace(1.0, 1.5, 64)  # tile 1: slightly larger scores
+    Q[5, 0] = 40.0                       # row 5 (group 0): its scores run ahead by far more than the slack
+    V[:, 0] = np.arange(N) / N
+    slack = 2.0
+    r = so.sparse_attention(Q, K, V, None, scale=1.0, quant=False, pv_dtype="bf16", ref_slack=slack)
+    S = Q @ K.T
+    for row, moved in ((5, True), (6, True), (40, False)):   # rows 5, 6 share group 0; row 40 is in group 1
+        m0 = S[row, :64].max()
+        m1 = S[row].max()
+        ref1 = m1 if moved else m0       # reference in force for tile 1
+        # tile 0 is rounded against m0; when the reference moves its contribution is rescaled exactly
+        p0 = so.round16(np.exp(S[row, :64] - m0), "bf16") * np.exp(m0 - ref1)
+        p1 = so.round16(np.exp(S[row, 64:] - ref1), "bf16")
+        l = np.exp(S[row, :64] - m0).sum() * np.exp(m0 - ref1) + np.exp(S[row, 64:] - ref1).sum()
+        want = (p0 @ V[:64, 0] + p1 @ V[64:, 0]) / l
+        assert abs(r.O[row, 0] - want) < 1e-12, (row, r.O[row, 0], want)
