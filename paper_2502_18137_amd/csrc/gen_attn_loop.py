@@ -25,6 +25,13 @@ goes: cntk tiles can be copied as whole blocks, cnt tiles exist); then one "step
 as a sequence of slots: operand read (LDS, three slots ahead), one MFMA, a chunk of the softmax.
 The row maximum of the fresh scores, the stage-2 test (Alg. 1 line 15) and the test whether the
 reference maximum must move follow at the end of the step; the block leaves when one of them says so.
+
+Two kinds of iteration bodies exist.  "fast": tile u+1 needs no element masks.  "masked": the scores
+of tile u+1 are overwritten in place with -inf where the key lies past N or (causal) past the row,
+before their row maximum is taken, so the softmax of the following iteration needs no mask; a tile
+u+1 that does not exist counts as fully masked, which makes the last iteration (u = cnt-1, nothing to
+score) and the drain (u = cnt: only P~V of the last tile) ordinary masked iterations.  Iteration 0
+runs with P[1] = 0 against a zero-filled V buffer.
 """
 import os
 
@@ -55,12 +62,13 @@ class Cfg:
         self.MLOC = 135
         self.KA, self.VA = 136, 140   # per-lane LDS addresses of the operand reads in buffer 0
         self.KSRC, self.VSRC = 144, 145
-        self.O = 146
+        self.L3, self.ROWLIM = 146, 147  # masked bodies: list prefetch of tile u+1; last visible key per lane
+        self.O = 148
         self.Q = self.O + 16 * self.NDT
         self.NVGPR = self.Q + 4 * self.NSTEP
         # ---- SGPRs (pinned) ----
-        names = ("u uend kb0 kb1 vb0 vb1 ldskd ldsvd ldsjl ldsscl lam2 exec need pv scx scn "
-                 "jk jv r negmagic rt scnn t0 t1 a0 a1 cnt cntk").split()
+        names = ("u ustop kb0 kb1 vb0 vb1 ldskd ldsvd ldsjl ldsscl lam2 exec need pv scx scn "
+                 "jk jv r negmagic rt scnn t0 t1 a0 a1 cnt cntk ufull maskok jn").split()
         self.sg = {n: 36 + i for i, n in enumerate(names)}
         assert self.sg["kb0"] % 2 == 0 and self.sg["vb0"] % 2 == 0 and self.sg["a0"] % 2 == 0, self.sg
 
@@ -69,7 +77,7 @@ def vr(b, n=1):
     return f"v{b}" if n == 1 else f"v[{b}:{b + n - 1}]"
 
 
-def gen_step(c, o, cur, NST, kbuf, vbuf):
+def gen_step(c, o, cur, NST, kbuf, vbuf, masked):
     """One iteration body: softmax of S[cur] -> P[cur]; scores of the next tile -> S[1-cur];
     O += P[1-cur] V; then the row maximum of the fresh scores and the two decisions."""
     s = c.sg
@@ -110,9 +118,19 @@ def gen_step(c, o, cur, NST, kbuf, vbuf):
         if k:
             A(2 * k - 2); A(2 * k - 1); C(k - 1)
     A(30); A(31); C(15)
-    first_max = len(ops)  # index of the first instruction that reads the fresh scores
-    # row maximum of the fresh scores (biased integers compare like the scores themselves)
+    first_max = len(ops)  # index of the first instruction that touches the fresh scores
     y = lambda e: YS + e
+    if masked:
+        # -inf over the scores of keys this lane's row must not see: key offset inside the tile >
+        # ROWLIM - 64 j (a tile that does not exist has everything masked); -inf is a negative integer,
+        # so the integer maximum below ignores it
+        ops.append((f"v_subrev_u32 v{T1}, s{s['t0']}, v{c.ROWLIM}", 1))
+        ops.append((f"v_mov_b32 v{T2}, 0xff800000", 1))
+        for e in range(32):
+            koff = (e >> 4) * 32 + 8 * ((e & 15) >> 2) + (e & 3)
+            ops.append((f"v_cmp_le_i32 vcc, {koff}, v{T1}", 1))
+            ops.append((f"v_cndmask_b32 v{y(e)}, v{T2}, v{y(e)}, vcc", 1))
+    # row maximum of the fresh scores (biased integers compare like the scores themselves)
     chains = []
     for t, base in ((T0, y(0)), (T1, y(16))):
         ch = [f"v_max3_i32 v{t}, v{base}, v{base + 1}, v{base + 2}"]
@@ -152,7 +170,7 @@ def gen_step(c, o, cur, NST, kbuf, vbuf):
     chunks[-1] += tail
     assert len(chunks[-1]) >= 12, "too little vector work behind the last MFMA"
 
-    o(f"; ---- step: softmax S{cur} -> P{cur} | scores -> S{nxt}, O += P{nxt} V")
+    o(f"; ---- {'masked' if masked else 'fast'} step: softmax S{cur} -> P{cur} | scores -> S{nxt}, O += P{nxt} V")
     # list entries the next iteration needs (older than every operand read of this step)
     o(f"s_lshl_b32 s{s['t0']}, s{s['u']}, 1")
     o(f"s_add_u32 s{s['t0']}, s{s['t0']}, s{s['ldsjl']}")
@@ -163,10 +181,16 @@ def gen_step(c, o, cur, NST, kbuf, vbuf):
     o(f"ds_read_u16 v{c.L1}, v{c.L0} offset:{2 * (NST - 1)}")   # key block of V(u+1+NST-2)
     o(f"ds_read_u16 v{c.L0}, v{c.L0} offset:{2 * (NST + 1)}")   # key block of K_hat(u+1+NST)
     o(f"ds_read_b32 v{c.L2}, v{c.L2} offset:8")                 # scale of tile u+2
+    if masked:
+        o(f"v_mov_b32 v{c.L3}, s{s['t0']}")
+        o(f"ds_read_u16 v{c.L3}, v{c.L3} offset:2")             # key block of tile u+1
     for sl in range(LA):
         read(sl)
     o(f"v_mov_b32 v{c.CX}, s{s['negmagic']}")
     o(f"v_fma_f32 v{c.CX}, v{c.CX}, s{s['scx']}, -v{c.MR}")   # -(bias * scale) - reference maximum
+    if masked:  # a row that has not seen a key yet (reference -inf) only has masked scores here
+        o(f"v_cmp_eq_f32 vcc, 0xff800000, v{c.MR}")
+        o(f"v_cndmask_b32_e64 v{c.CX}, v{c.CX}, 0, vcc")
     o(f"s_add_u32 s{s['pv']}, s{s['pv']}, 1")
     for t in chunks[0]:
         o(t)
@@ -179,6 +203,13 @@ def gen_step(c, o, cur, NST, kbuf, vbuf):
             o(f"v_readfirstlane_b32 s{s['jk']}, v{c.L0}")
             o(f"v_readfirstlane_b32 s{s['jv']}, v{c.L1}")
             o(f"v_readfirstlane_b32 s{s['scnn']}, v{c.L2}")
+            if masked:
+                o(f"v_readfirstlane_b32 s{s['jn']}, v{c.L3}")
+                o(f"s_lshl_b32 s{s['t0']}, s{s['jn']}, 6")
+                o(f"s_add_u32 s{s['t1']}, s{s['u']}, 1")
+                o(f"s_cmp_lt_u32 s{s['t1']}, s{s['cnt']}")
+                o(f"s_cselect_b32 s{s['t0']}, s{s['t0']}, 0x40000000")   # no tile u+1: mask everything
+                o(f"s_cselect_b32 s{s['scn']}, s{s['scn']}, 1.0")        # and do not use a scale from past the list
         for t in chunks[sl + 1]:
             o(t)
     # stage-2 decision of the new tile; has the maximum run away from the reference?
@@ -194,6 +225,7 @@ def gen_step(c, o, cur, NST, kbuf, vbuf):
 
 
 def gen_top(c, o, NST, dkbuf, dvbuf, r, late):
+    r = f"{r}"  # label suffix (fast and masked bodies have their own)
     """Top of an iteration: wait, barrier, the wave's share of the next tile copies.  Copies are issued
     in groups {K_hat(t+1), V(t-1)}, group u+NST-1 here; near the end of the list a group shrinks."""
     s = c.sg
@@ -204,7 +236,10 @@ def gen_top(c, o, NST, dkbuf, dvbuf, r, late):
         o(f"s_cbranch_scc0 L_tailw{r}_%=")
         o(f"s_waitcnt vmcnt({c.NDMA})")
         o(f"L_waited{r}_%=:")
-        late.append((f"L_tailw{r}_%=", [f"s_waitcnt vmcnt({c.VD})", f"s_branch L_waited{r}_%="]))
+        late.append((f"L_tailw{r}_%=", [f"s_cmp_lt_u32 s{s['u']}, s{s['cnt']}",
+                                         f"s_cbranch_scc0 L_tailw0_{r}_%=",
+                                         f"s_waitcnt vmcnt({c.VD})", f"s_branch L_waited{r}_%=",
+                                         f"L_tailw0_{r}_%=:", "s_waitcnt vmcnt(0)", f"s_branch L_waited{r}_%="]))
     else:
         assert NST == 2
         o("s_waitcnt vmcnt(0)")
@@ -240,36 +275,54 @@ def gen_top(c, o, NST, dkbuf, dvbuf, r, late):
     o(f"L_skipv{r}_%=:")
 
 
-def gen_check(c, o, go):
+def gen_go(c, o, r):
+    """Which body runs iteration u = r (mod period), if any.  u has been counted up already."""
     s = c.sg
-    o(f"s_cmp_ge_u32 s{s['u']}, s{s['uend']}")
+    o(f"L_go{r}_%=:")
+    o(f"s_cmp_ge_u32 s{s['u']}, s{s['ustop']}")
     o("s_cbranch_scc1 L_exit_%=")
+    o(f"s_cmp_lg_u32 s{s['need']}, 0")
+    o("s_cbranch_scc1 L_exit_%=")
+    o(f"s_cmp_ge_u32 s{s['u']}, s{s['cnt']}")
+    o(f"s_cbranch_scc1 L_drain{r}_%=")
     o(f"s_cmp_eq_u32 s{s['exec']}, 0")
     o("s_cbranch_scc1 L_exit_%=")
-    o(f"s_cmp_eq_u32 s{s['need']}, 0")
-    o(f"s_cbranch_scc1 {go}")
-    o("s_branch L_exit_%=")
+    o(f"s_add_u32 s{s['t0']}, s{s['u']}, 1")
+    o(f"s_cmp_lt_u32 s{s['t0']}, s{s['ufull']}")
+    o(f"s_cbranch_scc0 L_tomask{r}_%=")
 
 
 def gen_loop(c, NST):
     s = c.sg
     lines = []
     o = lines.append
-    period = 2 * NST if NST % 2 else NST  # bodies: one per value of u mod lcm(2, NST)
+    period = 2 * NST if NST % 2 else NST  # bodies: one pair per value of u mod lcm(2, NST)
     o(f"s_mov_b32 s{s['negmagic']}, 0x{MAGIC_NEG:08x}")
     o(f"s_mov_b32 s{s['rt']}, 0x{RESCALE_T:08x}")
     o("s_waitcnt vmcnt(0) lgkmcnt(0)")
     for r in range(1, period):
         o(f"s_cmp_eq_u32 s{s['r']}, {r}")
-        o(f"s_cbranch_scc1 L_body{r}_%=")
+        o(f"s_cbranch_scc1 L_go{r}_%=")
     late = []  # out-of-line pieces: (label, instructions)
     for r in range(period):
-        o(f"L_body{r}_%=:")
         # iteration u = r (mod period): K_hat(u+1) in buffer (u+1) % NST, V(u-1) in (u-1) % NST;
         # the new copies go to u % NST (K_hat) and (u-2) % NST (V)
-        gen_top(c, o, NST, r % NST, (r - 2) % NST, r, late)
-        gen_step(c, o, r & 1, NST, (r + 1) % NST, (r - 1) % NST)
-        gen_check(c, o, f"L_body{(r + 1) % period}_%=")
+        gen_go(c, o, r)
+        gen_top(c, o, NST, r % NST, (r - 2) % NST, f"f{r}", late)
+        gen_step(c, o, r & 1, NST, (r + 1) % NST, (r - 1) % NST, False)
+        if r == period - 1:
+            o("s_branch L_go0_%=")
+    for r in range(period):
+        # the drain (u = cnt) runs the pending P~V of the last tile; past it the block is done
+        o(f"L_drain{r}_%=:")
+        o(f"s_cmp_eq_u32 s{s['u']}, s{s['cnt']}")
+        o("s_cbranch_scc0 L_exit_%=")
+        o(f"L_tomask{r}_%=:")
+        o(f"s_cmp_eq_u32 s{s['maskok']}, 0")
+        o("s_cbranch_scc1 L_exit_%=")
+        gen_top(c, o, NST, r % NST, (r - 2) % NST, f"m{r}", late)
+        gen_step(c, o, r & 1, NST, (r + 1) % NST, (r - 1) % NST, True)
+        o(f"s_branch L_go{(r + 1) % period}_%=")
     for label, ins in late:
         o(label + ":")
         for i in ins:
@@ -280,8 +333,8 @@ def gen_loop(c, NST):
 
 
 def clobbers(c):
-    v = list(range(c.RG, c.RG + 16)) + list(range(c.T, c.T + 3)) + [c.CX]
-    sg = [c.sg[n] for n in "negmagic rt scnn t0 t1 a0 a1".split()]
+    v = list(range(c.RG, c.RG + 16)) + list(range(c.T, c.T + 3)) + [c.CX, c.L3]
+    sg = [c.sg[n] for n in "negmagic rt scnn t0 t1 a0 a1 jn".split()]
     return [f"v{i}" for i in v] + [f"s{i}" for i in sg] + ["vcc", "scc", "memory"]
 
 
@@ -314,6 +367,7 @@ def gen_function(c, NST):
         ins.append(f'"{{{vr(c.Q + 4 * st, 4)}}}"(w.qf[{st}])')
     ins.append(f'"{{{vr(c.MG, 16)}}}"(magic)')
     ins.append(f'"{{v{c.INV}}}"(p.inval)')
+    ins.append(f'"{{v{c.ROWLIM}}}"(p.rowlim)')
     for st in range(c.NSTEP):
         ins.append(f'"{{v{c.KA + st}}}"(p.k_adr[{st}])')
     for ks in range(4):
@@ -322,7 +376,7 @@ def gen_function(c, NST):
     ins.append(f'"{{v{c.VSRC}}}"(p.v_src)')
     ins.append(f'"{{s[{s["kb0"]}:{s["kb1"]}]}}"(p.kbase)')
     ins.append(f'"{{s[{s["vb0"]}:{s["vb1"]}]}}"(p.vbase)')
-    for n in "r uend cnt cntk ldskd ldsvd ldsjl ldsscl lam2".split():
+    for n in "r ustop cnt cntk ufull maskok ldskd ldsvd ldsjl ldsscl lam2".split():
         ins.append(f'"{{s{s[n]}}}"(p.{n})')
     w("            : " + ",\n              ".join(outs))
     w("            : " + ",\n              ".join(ins))
