@@ -30,7 +30,7 @@ PEAK_HBM = 8.0e12    # B/s
 # HBM-side bytes per launch of the attention kernel (read + written), from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs of this script scaled by a 1 GiB copy (profiles/attn_kernel_hbm_traffic.txt).  They belong
 # to the default workloads with all heads; any other run reports null.
-MEASURED_TRAFFIC_BYTES = {"longvideo": 60.3e9 + 0.283e9, "video": 0.325e9 + 0.108e9}
+MEASURED_TRAFFIC_BYTES = {"longvideo": 63.2e9 + 2.81e9, "video": 1.61e9 + 1.34e9}
 
 
 CONFIGS_H = {"longvideo": 24, "video": 48}
