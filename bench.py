@@ -198,6 +198,65 @@ def cpu_baseline(w, data, mask_gpu, budget_blocks=None):
     }
 
 
+def sweep_sparsity(steps):
+    """Kernel speed against block sparsity (the paper's kernel-speed figure, Sec. 4.3): random block masks
+    of a forced density at N = 22 272 (the 22K of the paper's Mochi setting), H = 24, d = 128, bf16, random
+    normal Q/K/V, lambda = -inf; the attention kernel alone, on operands quantized and tiled beforehand."""
+    import torch
+    import paper_2502_18137_amd as sp
+    H, N, d = 24, 22272, 128
+    g = torch.Generator(device="cuda").manual_seed(0)
+    Q, K, V = (torch.randn((1, H, N, d), device="cuda", generator=g).to(torch.bfloat16) for _ in range(3))
+    Qq, Kq, qs, ks, _ = sp.sparge_quantize(Q, K)
+    vt = sp.sparge_v_tiles(V)
+    O = torch.empty_like(V)
+    Tm, Tn = (N + 127) // 128, (N + 63) // 64
+    ops = 4.0 * N * N * d * H
+    rows = []
+    for target in (0.0, 0.1, 0.2, 0.3, 0.4, 0.5, 0.6, 0.7, 0.8, 0.9):
+        mask = (torch.rand((1, H, Tm, Tn), device="cuda", generator=g) >= target).to(torch.uint8)
+        mask[..., 0] = 1
+        st = torch.zeros((1, H, 4), dtype=torch.int64, device="cuda")
+        sp.sparge_attn_tiled(Qq, Kq, qs, ks, vt, V, mask, -math.inf, out=O, stats=st)
+        st = st.cpu().numpy()
+        ms = event_time(lambda: sp.sparge_attn_tiled(Qq, Kq, qs, ks, vt, V, mask, -math.inf, out=O), reps=steps, warmup=2)
+        qk_ops, pv_flops = executed_ops(st, d)
+        rows.append({"sparsity": sparsity_of(st), "attn_ms": ms, "dense_equiv_tops": ops / (ms * 1e-3) / 1e12,
+                     "mfma_frac": (qk_ops / PEAK_INT8 + pv_flops / PEAK_16) / (ms * 1e-3)})
+        log(f"  sparsity {rows[-1]['sparsity']:.2f}: {ms:.3f} ms, {rows[-1]['dense_equiv_tops']:.0f} dense-equivalent TOPS, "
+            f"MFMA frac {rows[-1]['mfma_frac']:.3f}")
+    return {"sweep": "sparsity", "workload": f"random block masks, B=1 H={H} N={N} d={d} bf16 non-causal, kernel only",
+            "unit": "TOPS (4*N^2*d*H / kernel time)", "rows": rows}
+
+
+def sweep_overhead(steps):
+    """Latency of the sparse-block prediction against the full attention latency over sequence lengths
+    (the paper's overhead table, Sec. 4.3): H = 32, d = 128 (the head geometry of the language model the
+    paper uses there), bf16, random normal Q/K/V."""
+    import torch
+    import paper_2502_18137_amd as sp
+    H, d = 32, 128
+    rows = []
+    for N in (8192, 16384, 32768, 65536, 131072):
+        g = torch.Generator(device="cuda").manual_seed(N)
+        Q, K, V = (torch.randn((1, H, N, d), device="cuda", generator=g).to(torch.bfloat16) for _ in range(3))
+        wsp = torch.empty(sp.sparge_workspace_bytes(Q, sp.WS_PREDICT), dtype=torch.uint8, device="cuda")
+        wsq = torch.empty(sp.sparge_workspace_bytes(Q, sp.WS_QUANTIZE), dtype=torch.uint8, device="cuda")
+        pred_ms = event_time(lambda: sp.sparge_predict(Q, K, 0.9, 0.5, ws=wsp), reps=steps)
+        quant_ms = event_time(lambda: sp.sparge_quantize(Q, K, ws=wsq), reps=steps)
+        Qq, Kq, qs, ks, _ = sp.sparge_quantize(Q, K)
+        vt = sp.sparge_v_tiles(V)
+        O = torch.empty_like(V)
+        full_ms = event_time(lambda: sp.sparge_attn_tiled(Qq, Kq, qs, ks, vt, V, None, -math.inf, out=O),
+                             reps=max(2, steps // 2), warmup=1)
+        rows.append({"N": N, "predict_ms": pred_ms, "quantize_ms": quant_ms, "full_attention_ms": full_ms,
+                     "overhead_pct": 100.0 * pred_ms / full_ms,
+                     "full_attention_tops": 4.0 * N * N * d * H / (full_ms * 1e-3) / 1e12})
+        log(f"  N={N}: predict {pred_ms:.3f} ms, full attention {full_ms:.3f} ms, overhead {rows[-1]['overhead_pct']:.2f} %")
+        del Q, K, V, Qq, Kq, vt, O, wsp, wsq
+    return {"sweep": "overhead", "workload": f"B=1 H={H} d={d} bf16 non-causal, tau=0.9 theta=0.5", "rows": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -212,7 +271,12 @@ def main():
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy, the known-size dispatch that HBM counter "
                          "readings (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) are scaled by")
+    ap.add_argument("--sweep", choices=["sparsity", "overhead"],
+                    help="print one of the paper's two kernel-level exhibits instead of the benchmark line")
     args = ap.parse_args()
+    if args.sweep:
+        print(json.dumps(sweep_sparsity(args.steps) if args.sweep == "sparsity" else sweep_overhead(args.steps)))
+        return
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (heads would shard with no "
               "exchange); run with --gpus 1", file=sys.stderr)

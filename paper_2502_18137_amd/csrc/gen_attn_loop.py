@@ -16,7 +16,7 @@ A wave owns one 32-row group.  The loop is skewed by one tile; tiles are positio
 of kept key blocks.  State at the boundary "top of iteration u" (u >= 1):
   S[u & 1]        biased scores of tile u; the row statistics already include tile u
                   (scx = its dequantization scale, exec = its stage-2 decision),
-  P[(u - 1) & 1]  P~ of tile u-1, waiting for its P~V product,
+  P[(u - 1) & 1]  P~ of tile u-1, waiting for its P~V product (execp = its stage-2 decision),
   LDS             K_hat(u+1) and V(u-1) have been requested NST-1 iterations ago.
 Iteration u: wait for own copies, barrier, request K_hat(u+NST) and V(u+NST-2) (as far as the list
 goes: cntk tiles can be copied as whole blocks, cnt tiles exist); then one "step":
@@ -24,14 +24,17 @@ goes: cntk tiles can be copied as whole blocks, cnt tiles exist); then one "step
   MFMA:       scores of tile u+1 -> S[(u + 1) & 1];  O += P~(u-1) V(u-1)
 as a sequence of slots: operand read (LDS, three slots ahead), one MFMA, a chunk of the softmax.
 The row maximum of the fresh scores, the stage-2 test (Alg. 1 line 15) and the test whether the
-reference maximum must move follow at the end of the step; the block leaves when one of them says so.
+reference maximum must move follow at the end of the step.  A move takes effect at once for l and
+m_ref; O is multiplied one iteration later, after the P~V product that was computed against the old
+reference has been added (havefo / fo carry that debt, also across the block's boundary).
 
+Every body exists with and without the P~V product (execp: the stage-2 decision of tile u-1).
 Two kinds of iteration bodies exist.  "fast": tile u+1 needs no element masks.  "masked": the scores
 of tile u+1 are overwritten in place with -inf where the key lies past N or (causal) past the row,
 before their row maximum is taken, so the softmax of the following iteration needs no mask; a tile
 u+1 that does not exist counts as fully masked, which makes the last iteration (u = cnt-1, nothing to
 score) and the drain (u = cnt: only P~V of the last tile) ordinary masked iterations.  Iteration 0
-runs with P[1] = 0 against a zero-filled V buffer.
+enters with execp = 0: nothing is pending.
 """
 import os
 
@@ -63,12 +66,13 @@ class Cfg:
         self.KA, self.VA = 136, 140   # per-lane LDS addresses of the operand reads in buffer 0
         self.KSRC, self.VSRC = 144, 145
         self.L3, self.ROWLIM = 146, 147  # masked bodies: list prefetch of tile u+1; last visible key per lane
-        self.O = 148
+        self.FO = 148                    # factor O still has to be multiplied by (the reference maximum moved)
+        self.O = 150                     # tuples start at even registers
         self.Q = self.O + 16 * self.NDT
         self.NVGPR = self.Q + 4 * self.NSTEP
         # ---- SGPRs (pinned) ----
         names = ("u ustop kb0 kb1 vb0 vb1 ldskd ldsvd ldsjl ldsscl lam2 exec need pv scx scn "
-                 "jk jv r negmagic rt scnn t0 t1 a0 a1 cnt cntk ufull maskok jn").split()
+                 "jk jv r negmagic rt scnn t0 t1 a0 a1 cnt cntk ufull maskok jn execp havefo").split()
         self.sg = {n: 36 + i for i, n in enumerate(names)}
         assert self.sg["kb0"] % 2 == 0 and self.sg["vb0"] % 2 == 0 and self.sg["a0"] % 2 == 0, self.sg
 
@@ -77,13 +81,16 @@ def vr(b, n=1):
     return f"v{b}" if n == 1 else f"v[{b}:{b + n - 1}]"
 
 
-def gen_step(c, o, cur, NST, kbuf, vbuf, masked):
+def gen_step(c, o, cur, NST, kbuf, vbuf, masked, pv):
     """One iteration body: softmax of S[cur] -> P[cur]; scores of the next tile -> S[1-cur];
-    O += P[1-cur] V; then the row maximum of the fresh scores and the two decisions."""
+    O += P[1-cur] V unless that product was voted out (pv = False: Alg. 1 line 15 said skip); then the
+    row maximum of the fresh scores and the two decisions."""
     s = c.sg
     nxt = 1 - cur
     XS, XP, YS, YP = c.S[cur], c.P[cur], c.S[nxt], c.P[nxt]
     T0, T1, T2 = c.T, c.T + 1, c.T + 2
+
+    NSLOT = c.NSLOT if pv else c.NQK  # without the P~V product only the score MFMAs remain
 
     def read(sl):
         dst = c.RG + 4 * (sl % RING)
@@ -153,24 +160,43 @@ def gen_step(c, o, cur, NST, kbuf, vbuf, masked):
             f"v_add_f32 v{T0}, v{T0}, v{c.INV}",              # rows past N: -inf
             f"v_add_f32 v{T1}, v{T1}, v{c.INV}"]
 
-    total = sum(u for _, u in ops)
-    per_slot = (total - PRE_UNITS) / c.NSLOT
     # chunk 0 runs before the first MFMA, chunk sl + 1 after MFMA sl
-    chunks, acc_u, idx = [], 0.0, 0
-    for k in range(c.NSLOT + 1):
-        target = PRE_UNITS + per_slot * k
-        ch = []
-        while idx < len(ops) and (acc_u + ops[idx][1] / 2 <= target or k == c.NSLOT):
-            if idx == first_max:
-                # the fresh scores are complete a few slots after the last Q K^T MFMA
-                assert k - 1 >= c.NQK + 1, "row-maximum work scheduled too early"
-            ch.append(ops[idx][0]); acc_u += ops[idx][1]
-            idx += 1
-        chunks.append(ch)
+    if pv:
+        total = sum(u for _, u in ops)
+        per_slot = (total - PRE_UNITS) / NSLOT
+        chunks, acc_u, idx = [], 0.0, 0
+        for k in range(NSLOT + 1):
+            target = PRE_UNITS + per_slot * k
+            ch = []
+            while idx < len(ops) and (acc_u + ops[idx][1] / 2 <= target or k == NSLOT):
+                if idx == first_max:
+                    # the fresh scores are complete a few slots after the last Q K^T MFMA
+                    assert k - 1 >= c.NQK + 1, "row-maximum work scheduled too early"
+                ch.append(ops[idx][0]); acc_u += ops[idx][1]
+                idx += 1
+            chunks.append(ch)
+    else:
+        # the score MFMAs are the only ones: the softmax stream is spread over their slots, at least 20
+        # of its instructions stay behind the last MFMA, and the work on the fresh scores follows them
+        soft, fresh = ops[:first_max], ops[first_max:]
+        keep_last = 20
+        head = soft[:len(soft) - keep_last]
+        total = sum(u for _, u in head)
+        per_slot = total / NSLOT
+        chunks, acc_u, idx = [], 0.0, 0
+        for k in range(NSLOT):
+            target = per_slot * (k + 1)
+            ch = []
+            while idx < len(head) and (acc_u + head[idx][1] / 2 <= target or k == NSLOT - 1):
+                ch.append(head[idx][0]); acc_u += head[idx][1]
+                idx += 1
+            chunks.append(ch)
+        chunks.append([t for t, _ in soft[len(soft) - keep_last:]] + [t for t, _ in fresh])
     chunks[-1] += tail
     assert len(chunks[-1]) >= 12, "too little vector work behind the last MFMA"
 
-    o(f"; ---- {'masked' if masked else 'fast'} step: softmax S{cur} -> P{cur} | scores -> S{nxt}, O += P{nxt} V")
+    o(f"; ---- {'masked' if masked else 'fast'} step: softmax S{cur} -> P{cur} | scores -> S{nxt}"
+      + (f", O += P{nxt} V" if pv else " (P~V voted out)"))
     # list entries the next iteration needs (older than every operand read of this step)
     o(f"s_lshl_b32 s{s['t0']}, s{s['u']}, 1")
     o(f"s_add_u32 s{s['t0']}, s{s['t0']}, s{s['ldsjl']}")
@@ -191,13 +217,14 @@ def gen_step(c, o, cur, NST, kbuf, vbuf, masked):
     if masked:  # a row that has not seen a key yet (reference -inf) only has masked scores here
         o(f"v_cmp_eq_f32 vcc, 0xff800000, v{c.MR}")
         o(f"v_cndmask_b32_e64 v{c.CX}, v{c.CX}, 0, vcc")
-    o(f"s_add_u32 s{s['pv']}, s{s['pv']}, 1")
+    if pv:
+        o(f"s_add_u32 s{s['pv']}, s{s['pv']}, 1")
     for t in chunks[0]:
         o(t)
-    for sl in range(c.NSLOT):
-        if sl + LA < c.NSLOT:
+    for sl in range(NSLOT):
+        if sl + LA < NSLOT:
             read(sl + LA)
-        o(f"s_waitcnt lgkmcnt({min(LA, c.NSLOT - 1 - sl)})")
+        o(f"s_waitcnt lgkmcnt({min(LA, NSLOT - 1 - sl)})")
         mfma(sl)
         if sl == 0:  # the list entries (older than the operand reads) have arrived
             o(f"v_readfirstlane_b32 s{s['jk']}, v{c.L0}")
@@ -213,6 +240,7 @@ def gen_step(c, o, cur, NST, kbuf, vbuf, masked):
         for t in chunks[sl + 1]:
             o(t)
     # stage-2 decision of the new tile; has the maximum run away from the reference?
+    o(f"s_mov_b32 s{s['execp']}, s{s['exec']}")   # the tile whose P~ was just made keeps its decision
     o(f"v_cmp_lt_f32 vcc, s{s['lam2']}, v{T0}")
     o("s_cmp_lg_u64 vcc, 0")
     o(f"s_cselect_b32 s{s['exec']}, 1, 0")
@@ -275,28 +303,54 @@ def gen_top(c, o, NST, dkbuf, dvbuf, r, late):
     o(f"L_skipv{r}_%=:")
 
 
+def gen_moves(c, o, tag, late):
+    """After a step: O *= fO if a move of the reference maximum is still owed to O (the P~V product that
+    was pending when the reference moved has now been added), then the move the step just asked for:
+    l and m_ref at once, O one iteration later.  Both are rare and live out of line."""
+    s = c.sg
+    T0 = c.T
+    o(f"s_cmp_lg_u32 s{s['havefo']}, 0")
+    o(f"s_cbranch_scc1 L_applyfo{tag}_%=")
+    o(f"L_afterfo{tag}_%=:")
+    o(f"s_cmp_lg_u32 s{s['need']}, 0")
+    o(f"s_cbranch_scc1 L_move{tag}_%=")
+    o(f"L_aftermove{tag}_%=:")
+    ins = ["s_nop 7", "s_nop 7", "s_nop 7"]    # the step's last MFMA results have landed
+    ins += [f"v_mul_f32 v{c.O + i}, v{c.O + i}, v{c.FO}" for i in range(16 * c.NDT)]
+    ins += [f"s_mov_b32 s{s['havefo']}, 0", "s_nop 3", f"s_branch L_afterfo{tag}_%="]
+    late.append((f"L_applyfo{tag}_%=", ins))
+    ins = [f"v_sub_f32 v{T0}, v{c.MR}, v{c.MT}",
+           f"v_exp_f32 v{T0}, v{T0}",
+           f"v_mov_b32 v{c.MR}, v{c.MT}",
+           "s_nop 0",
+           f"v_mul_f32 v{c.L}, v{c.L}, v{T0}",
+           f"v_mov_b32 v{c.FO}, v{T0}",
+           f"s_mov_b32 s{s['havefo']}, 1",
+           f"s_mov_b32 s{s['need']}, 0",
+           f"s_branch L_aftermove{tag}_%="]
+    late.append((f"L_move{tag}_%=", ins))
+
+
 def gen_go(c, o, r):
     """Which body runs iteration u = r (mod period), if any.  u has been counted up already."""
     s = c.sg
     o(f"L_go{r}_%=:")
     o(f"s_cmp_ge_u32 s{s['u']}, s{s['ustop']}")
     o("s_cbranch_scc1 L_exit_%=")
-    o(f"s_cmp_lg_u32 s{s['need']}, 0")
-    o("s_cbranch_scc1 L_exit_%=")
     o(f"s_cmp_ge_u32 s{s['u']}, s{s['cnt']}")
     o(f"s_cbranch_scc1 L_drain{r}_%=")
-    o(f"s_cmp_eq_u32 s{s['exec']}, 0")
-    o("s_cbranch_scc1 L_exit_%=")
     o(f"s_add_u32 s{s['t0']}, s{s['u']}, 1")
     o(f"s_cmp_lt_u32 s{s['t0']}, s{s['ufull']}")
     o(f"s_cbranch_scc0 L_tomask{r}_%=")
+    o(f"s_cmp_eq_u32 s{s['execp']}, 0")
+    o(f"s_cbranch_scc1 L_fastnopv{r}_%=")
 
 
 def gen_loop(c, NST):
     s = c.sg
     lines = []
     o = lines.append
-    period = 2 * NST if NST % 2 else NST  # bodies: one pair per value of u mod lcm(2, NST)
+    period = 2 * NST if NST % 2 else NST  # bodies: one set per value of u mod lcm(2, NST)
     o(f"s_mov_b32 s{s['negmagic']}, 0x{MAGIC_NEG:08x}")
     o(f"s_mov_b32 s{s['rt']}, 0x{RESCALE_T:08x}")
     o("s_waitcnt vmcnt(0) lgkmcnt(0)")
@@ -304,25 +358,40 @@ def gen_loop(c, NST):
         o(f"s_cmp_eq_u32 s{s['r']}, {r}")
         o(f"s_cbranch_scc1 L_go{r}_%=")
     late = []  # out-of-line pieces: (label, instructions)
-    for r in range(period):
+
+    def body(r, masked, pv, tag):
         # iteration u = r (mod period): K_hat(u+1) in buffer (u+1) % NST, V(u-1) in (u-1) % NST;
         # the new copies go to u % NST (K_hat) and (u-2) % NST (V)
+        gen_top(c, o, NST, r % NST, (r - 2) % NST, f"{tag}{r}", late)
+        gen_step(c, o, r & 1, NST, (r + 1) % NST, (r - 1) % NST, masked, pv)
+        gen_moves(c, o, f"{tag}{r}", late)
+
+    for r in range(period):
         gen_go(c, o, r)
-        gen_top(c, o, NST, r % NST, (r - 2) % NST, f"f{r}", late)
-        gen_step(c, o, r & 1, NST, (r + 1) % NST, (r - 1) % NST, False)
+        body(r, False, True, "f")
         if r == period - 1:
             o("s_branch L_go0_%=")
     for r in range(period):
-        # the drain (u = cnt) runs the pending P~V of the last tile; past it the block is done
+        nxt = f"s_branch L_go{(r + 1) % period}_%="
+        o(f"L_fastnopv{r}_%=:")
+        body(r, False, False, "g")
+        o(nxt)
+        # the drain (u = cnt) runs the pending P~V of the last tile if it was voted in; then the block is done
         o(f"L_drain{r}_%=:")
         o(f"s_cmp_eq_u32 s{s['u']}, s{s['cnt']}")
         o("s_cbranch_scc0 L_exit_%=")
+        o(f"s_cmp_eq_u32 s{s['execp']}, 0")
+        o("s_cbranch_scc1 L_exit_%=")
         o(f"L_tomask{r}_%=:")
         o(f"s_cmp_eq_u32 s{s['maskok']}, 0")
         o("s_cbranch_scc1 L_exit_%=")
-        gen_top(c, o, NST, r % NST, (r - 2) % NST, f"m{r}", late)
-        gen_step(c, o, r & 1, NST, (r + 1) % NST, (r - 1) % NST, True)
-        o(f"s_branch L_go{(r + 1) % period}_%=")
+        o(f"s_cmp_eq_u32 s{s['execp']}, 0")
+        o(f"s_cbranch_scc1 L_masknopv{r}_%=")
+        body(r, True, True, "m")
+        o(nxt)
+        o(f"L_masknopv{r}_%=:")
+        body(r, True, False, "n")
+        o(nxt)
     for label, ins in late:
         o(label + ":")
         for i in ins:
@@ -361,7 +430,8 @@ def gen_function(c, NST):
             outs.append(f'"+{{{vr(c.P[b] + 4 * ks, 4)}}}"(w.P[{b}][{ks}])')
     for reg, expr in ((c.MT, "w.m_true"), (c.MR, "w.m_ref"), (c.L, "w.l")):
         outs.append(f'"+{{v{reg}}}"({expr})')
-    for n in "u jk jv scn scx exec need pv".split():
+    outs.append(f'"+{{v{c.FO}}}"(p.fo)')
+    for n in "u jk jv scn scx exec execp need havefo pv".split():
         outs.append(f'"+{{s{s[n]}}}"(p.{n})')
     for st in range(c.NSTEP):
         ins.append(f'"{{{vr(c.Q + 4 * st, 4)}}}"(w.qf[{st}])')

@@ -98,3 +98,46 @@ def test_full_configuration(sp, name):
         print(f"  head {h}: {len(blocks)} Q blocks, rel-L1 vs oracle {err:.2e}, dont-care {int(pred.dont_care.sum())}",
               flush=True)
         assert err <= 2e-3
+
+
+@pytest.mark.parametrize("causal,dtype,d", [(False, "bf16", 128), (True, "fp16", 64)])
+def test_long_list_two_stage_kernel(sp, causal, dtype, d):
+    """T_n > 1024 selects the kernel variant with two LDS stages and the long tile list: N = 70 000
+    (ragged: last Q block 112 rows, last K block 48 keys), one head, a random block mask with a forced
+    first column (and diagonal when causal); the output rows of a few Q blocks against the oracle loop."""
+    import torch
+    from tests.helpers import small_workload
+    N = 70000
+    w = small_workload(name="long", N=N, d=d, dtype=dtype, H=1, causal=causal, lam=-6.0, seed=11, segment=512)
+    x = make_workload(w)
+    Q, K, V = (to_torch(x[t], w.dtype) for t in "qkv")
+    Tm, Tn = so.nblocks(N, 128), so.nblocks(N, 64)
+    assert Tn > 1024
+    rng = np.random.default_rng(5)
+    mask_np = (rng.random((1, 1, Tm, Tn)) < 0.3).astype(np.uint8)
+    mask_np[..., 0] = 1
+    if causal:
+        mask_np[0, 0, np.arange(Tm), np.minimum(2 * np.arange(Tm), Tn - 1)] = 1
+    mask_np[0, 0, -1, -1] = 1   # the partial last key block is used by the ragged last Q block
+    mask_t = torch.from_numpy(mask_np).to("cuda")
+    O, stats = sp.sparge_attn(Q, K, V, mask_t, w.lam, causal=causal, return_stats=True)
+    torch.cuda.synchronize()
+    assert torch.isfinite(O.float()).all()
+    q, k, v = x["q"][0, 0], x["k"][0, 0], x["v"][0, 0]
+    blocks = [0, 1, Tm // 3, Tm - 2, Tm - 1]
+    ref = so.sparse_attention(q, k, v, mask_np[0, 0], lam=f32(w.lam), causal=causal, quant=True, pv_dtype=dtype,
+                              q_blocks=blocks, ref_slack=REF_SLACK)
+    assert ref.zero_rows == 0
+    rows = np.concatenate([np.arange(128 * i, min(128 * (i + 1), N)) for i in blocks])
+    got = O[0, 0].float().cpu().numpy().astype(np.float64)[rows]
+    err = so.rel_l1(got, so.round16(ref.O[rows], dtype))
+    print(f"  long list causal={causal}: rel-L1 vs oracle {err:.2e}", flush=True)
+    assert err <= 2e-3
+    tiles, groups = closed_form_valid(N, causal)
+    s = stats.cpu().numpy()[0, 0]
+    assert s[2] == tiles and s[3] == groups
+    visible = mask_np[0, 0].astype(bool)
+    if causal:
+        for i in range(Tm):
+            visible[i, np.arange(Tn) * 64 > i * 128 + 127] = False
+    assert s[0] == visible.sum()
