@@ -19,7 +19,7 @@ of kept key blocks.  State at the boundary "top of iteration u" (u >= 1):
   P[(u - 1) & 1]  P~ of tile u-1, waiting for its P~V product (execp = its stage-2 decision),
   LDS             K_hat(u+1) and V(u-1) have been requested NST-1 iterations ago.
 Iteration u: wait for own copies, barrier, request K_hat(u+NST) and V(u+NST-2) (as far as the list
-goes: cntk tiles can be copied as whole blocks, cnt tiles exist); then one "step":
+goes; a partial last K_hat block is copied with clamped rows); then one "step":
   vector ALU: softmax of tile u  ->  P[u & 1], row sum
   MFMA:       scores of tile u+1 -> S[(u + 1) & 1];  O += P~(u-1) V(u-1)
 as a sequence of slots: operand read (LDS, three slots ahead), one MFMA, a chunk of the softmax.
@@ -67,12 +67,13 @@ class Cfg:
         self.KSRC, self.VSRC = 144, 145
         self.L3, self.ROWLIM = 146, 147  # masked bodies: list prefetch of tile u+1; last visible key per lane
         self.FO = 148                    # factor O still has to be multiplied by (the reference maximum moved)
-        self.O = 150                     # tuples start at even registers
+        self.KSRCC = 150                 # KD registers: copy offsets for a partial last K_hat block (rows clamped)
+        self.O = 152                     # tuples start at even registers
         self.Q = self.O + 16 * self.NDT
         self.NVGPR = self.Q + 4 * self.NSTEP
         # ---- SGPRs (pinned) ----
-        names = ("u ustop kb0 kb1 vb0 vb1 ldskd ldsvd ldsjl ldsscl lam2 exec need pv scx scn "
-                 "jk jv r negmagic rt scnn t0 t1 a0 a1 cnt cntk ufull maskok jn execp havefo").split()
+        names = ("u jpart kb0 kb1 vb0 vb1 ldskd ldsvd ldsjl ldsscl lam2 exec need pv scx scn "
+                 "jk jv r negmagic rt scnn t0 t1 a0 a1 cnt ufull jn execp havefo").split()
         self.sg = {n: 36 + i for i, n in enumerate(names)}
         assert self.sg["kb0"] % 2 == 0 and self.sg["vb0"] % 2 == 0 and self.sg["a0"] % 2 == 0, self.sg
 
@@ -260,7 +261,7 @@ def gen_top(c, o, NST, dkbuf, dvbuf, r, late):
     if NST == 3:
         # younger than the group this iteration needs: group u+1 = {K_hat(u+2), V(u)}
         o(f"s_add_u32 s{s['t0']}, s{s['u']}, 2")
-        o(f"s_cmp_lt_u32 s{s['t0']}, s{s['cntk']}")
+        o(f"s_cmp_lt_u32 s{s['t0']}, s{s['cnt']}")
         o(f"s_cbranch_scc0 L_tailw{r}_%=")
         o(f"s_waitcnt vmcnt({c.NDMA})")
         o(f"L_waited{r}_%=:")
@@ -274,11 +275,19 @@ def gen_top(c, o, NST, dkbuf, dvbuf, r, late):
     o("s_barrier")
     # LDS-DMA: this wave's pieces of K_hat(jk) and V(jv)
     o(f"s_add_u32 s{s['t0']}, s{s['u']}, {NST}")
-    o(f"s_cmp_lt_u32 s{s['t0']}, s{s['cntk']}")
+    o(f"s_cmp_lt_u32 s{s['t0']}, s{s['cnt']}")
     o(f"s_cbranch_scc0 L_skipk{r}_%=")
     o(f"s_mul_i32 s{s['t0']}, s{s['jk']}, {c.K_BYTES}")
     o(f"s_add_u32 s{s['a0']}, s{s['kb0']}, s{s['t0']}")
     o(f"s_addc_u32 s{s['a1']}, s{s['kb1']}, 0")
+    # the partial last key block is copied with its rows clamped to the last valid one
+    o(f"s_cmp_eq_u32 s{s['jk']}, s{s['jpart']}")
+    o(f"s_cbranch_scc1 L_kclamp{r}_%=")
+    ins = []
+    for n in range(c.KD):
+        ins += [f"s_add_u32 m0, s{s['ldskd']}, {dkbuf * c.K_BYTES + n * 1024 * NWAVE}", "s_nop 0",
+                f"global_load_lds_dwordx4 v{c.KSRCC + n}, s[{s['a0']}:{s['a1']}]"]
+    late.append((f"L_kclamp{r}_%=", ins + [f"s_branch L_skipk{r}_%="]))
     for n in range(c.KD):
         if n:  # the wave's next piece lies 4 KB further on both sides
             o(f"s_add_u32 s{s['a0']}, s{s['a0']}, {1024 * NWAVE}")
@@ -335,8 +344,6 @@ def gen_go(c, o, r):
     """Which body runs iteration u = r (mod period), if any.  u has been counted up already."""
     s = c.sg
     o(f"L_go{r}_%=:")
-    o(f"s_cmp_ge_u32 s{s['u']}, s{s['ustop']}")
-    o("s_cbranch_scc1 L_exit_%=")
     o(f"s_cmp_ge_u32 s{s['u']}, s{s['cnt']}")
     o(f"s_cbranch_scc1 L_drain{r}_%=")
     o(f"s_add_u32 s{s['t0']}, s{s['u']}, 1")
@@ -383,8 +390,6 @@ def gen_loop(c, NST):
         o(f"s_cmp_eq_u32 s{s['execp']}, 0")
         o("s_cbranch_scc1 L_exit_%=")
         o(f"L_tomask{r}_%=:")
-        o(f"s_cmp_eq_u32 s{s['maskok']}, 0")
-        o("s_cbranch_scc1 L_exit_%=")
         o(f"s_cmp_eq_u32 s{s['execp']}, 0")
         o(f"s_cbranch_scc1 L_masknopv{r}_%=")
         body(r, True, True, "m")
@@ -417,6 +422,11 @@ def gen_function(c, NST):
     w(f"template <> struct FastLoop<{c.D}, {dtn}, {NST}> {{")
     w("    template <class St>")
     w("    static __device__ __forceinline__ void run(St& w, const v16i& magic, FastLoopArgs& p) {")
+    for n in "u jk jv scn scx exec execp need havefo pv r jpart cnt ufull ldskd ldsvd ldsjl ldsscl lam2".split():
+        if n in ("scn", "scx", "lam2"):
+            w(f"        float {n}_ = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(p.{n})));")
+        else:
+            w(f"        int {n}_ = __builtin_amdgcn_readfirstlane(static_cast<int>(p.{n}));")
     w("        asm volatile(")
     for l in body:
         w(f'            "{l}\\n"')
@@ -431,8 +441,12 @@ def gen_function(c, NST):
     for reg, expr in ((c.MT, "w.m_true"), (c.MR, "w.m_ref"), (c.L, "w.l")):
         outs.append(f'"+{{v{reg}}}"({expr})')
     outs.append(f'"+{{v{c.FO}}}"(p.fo)')
-    for n in "u jk jv scn scx exec execp need havefo pv".split():
-        outs.append(f'"+{{s{s[n]}}}"(p.{n})')
+    # scalar operands go through readfirstlane copies: the register allocator then knows they are uniform
+    io_names = "u jk jv scn scx exec execp need havefo pv".split()
+    in_names = "r jpart cnt ufull ldskd ldsvd ldsjl ldsscl lam2".split()
+    floats = {"scn", "scx", "lam2"}
+    for n in io_names:
+        outs.append(f'"+{{s{s[n]}}}"({n}_)')
     for st in range(c.NSTEP):
         ins.append(f'"{{{vr(c.Q + 4 * st, 4)}}}"(w.qf[{st}])')
     ins.append(f'"{{{vr(c.MG, 16)}}}"(magic)')
@@ -443,14 +457,18 @@ def gen_function(c, NST):
     for ks in range(4):
         ins.append(f'"{{v{c.VA + ks}}}"(p.v_adr[{ks}])')
     ins.append(f'"{{v{c.KSRC}}}"(p.k_src)')
+    for n in range(c.KD):
+        ins.append(f'"{{v{c.KSRCC + n}}}"(p.k_src_clamped[{n}])')
     ins.append(f'"{{v{c.VSRC}}}"(p.v_src)')
     ins.append(f'"{{s[{s["kb0"]}:{s["kb1"]}]}}"(p.kbase)')
     ins.append(f'"{{s[{s["vb0"]}:{s["vb1"]}]}}"(p.vbase)')
-    for n in "r ustop cnt cntk ufull maskok ldskd ldsvd ldsjl ldsscl lam2".split():
-        ins.append(f'"{{s{s[n]}}}"(p.{n})')
+    for n in in_names:
+        ins.append(f'"{{s{s[n]}}}"({n}_)')
     w("            : " + ",\n              ".join(outs))
     w("            : " + ",\n              ".join(ins))
     w("            : " + ", ".join(f'"{x}"' for x in clobbers(c)) + ");")
+    for n in "u jk jv scn scx exec execp need havefo pv".split():
+        w(f"        p.{n} = {n}_;")
     w("    }")
     w("};")
     w("")
