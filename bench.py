@@ -30,7 +30,7 @@ PEAK_HBM = 8.0e12    # B/s
 # HBM-side bytes per launch of the attention kernel (read + written), from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs of this script scaled by a 1 GiB copy (profiles/attn_kernel_hbm_traffic.txt).  They belong
 # to the default workloads with all heads; any other run reports null.
-MEASURED_TRAFFIC_BYTES = {"longvideo": 63.2e9 + 2.81e9, "video": 1.61e9 + 1.34e9}
+MEASURED_TRAFFIC_BYTES = {"longvideo": 60.34e9 + 0.2835e9, "video": 0.341e9 + 0.1081e9}
 
 
 CONFIGS_H = {"longvideo": 24, "video": 48}
@@ -292,7 +292,7 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    names = [args.workload] + ([] if args.no_also or args.also == args.workload else [args.also])
+    names = [args.workload] + ([] if args.no_also else [n for n in args.also.split(",") if n and n != args.workload])
     workers = min(16, os.cpu_count() or 1)
     results, cpu = {}, None
     for name in names:
