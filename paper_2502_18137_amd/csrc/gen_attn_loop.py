@@ -1,16 +1,17 @@
 #!/usr/bin/env python3
-"""Writes attn_loop_gfx950.inc: the steady-state iterations of the sparse flash loop (Alg. 1 lines
-9-17 of arXiv 2502.18137 on full, unmasked tiles) as one hand-scheduled gfx950 assembly block per
-(head dimension, 16-bit type, LDS stages), wrapped in a C++ function that attn.hip includes.
+"""Writes attn_loop_gfx950.inc: the iterations of the sparse flash loop (Alg. 1 lines 9-17 of
+arXiv 2502.18137) as one hand-scheduled gfx950 assembly block per (head dimension, 16-bit type, LDS
+stages), wrapped in a C++ function that attn.hip includes.
 
     python gen_attn_loop.py            # rewrites attn_loop_gfx950.inc next to this file
 
 Why assembly: the matrix pipe and the vector ALU of a SIMD only overlap when MFMA and vector
 instructions alternate at fine grain inside a wave, and one wave alone cannot issue vector
 instructions back to back, so the kernel runs two waves per SIMD with 256 registers each; the
-instruction order and the register assignment are the design.  The block is entered at an iteration
-boundary of the kernel's main loop and leaves at one; everything irregular (first and last tiles,
-tiles that need element masks, skipped P~V products, moving the reference maximum) stays in C++.
+instruction order and the register assignment are the design.  The block is entered once per row
+group, after the kernel has computed the scores of the row's first kept tile, and runs every
+iteration including the last one and the drain; C++ keeps the list building, that first tile and the
+epilogue.
 
 A wave owns one 32-row group.  The loop is skewed by one tile; tiles are positions in the row's list
 of kept key blocks.  State at the boundary "top of iteration u" (u >= 1):
