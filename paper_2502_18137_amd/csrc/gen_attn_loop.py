@@ -41,8 +41,8 @@ import os
 
 MAGIC_NEG = 0xCB400000  # bit pattern of -12582912.0f = -(1.5 * 2^23)
 RESCALE_T = 0x41000000  # 8.0f
-LA = 3                  # operand reads run this many slots ahead
-RING = LA + 1
+LA = 4                  # operand reads run this many slots ahead; they are issued and awaited in pairs
+RING = LA + 2
 PRE_UNITS = 10          # vector work placed before the first MFMA of a step (covers the LDS latency)
 NWAVE = 4               # waves per workgroup sharing the tile copies
 
@@ -59,31 +59,46 @@ class Cfg:
         # ---- VGPRs (pinned; the kernel uses no AGPRs, so all 256 registers of a wave are VGPRs) ----
         self.S = (0, 32)
         self.P = (64, 80)
-        self.MG, self.RG = 96, 112
-        (self.MT, self.MR, self.L, self.INV, self.CX) = range(128, 133)
-        self.T = 133                              # 3 temporaries
-        self.L0, self.L1, self.L2 = 133, 134, 135  # list prefetch: read back before the temporaries are used
-        self.MLOC = 135
-        self.KA, self.VA = 136, 140   # per-lane LDS addresses of the operand reads in buffer 0
-        self.KSRC, self.VSRC = 144, 145
-        self.L3, self.ROWLIM = 146, 147  # masked bodies: list prefetch of tile u+1; last visible key per lane
-        self.FO = 148                    # factor O still has to be multiplied by (the reference maximum moved)
-        self.KSRCC = 150                 # KD registers: copy offsets for a partial last K_hat block (rows clamped)
-        self.O = 152                     # tuples start at even registers
+        self.MG, self.RG = 96, 112                # accumulator start value; ring of operand registers
+        nxt = self.RG + 4 * RING
+        (self.MT, self.MR, self.L, self.INV, self.CX) = range(nxt, nxt + 5)
+        nxt += 5
+        self.T = nxt                              # 3 temporaries
+        self.L0, self.L1, self.L2 = nxt, nxt + 1, nxt + 2  # list prefetch: read back before the temporaries are used
+        self.MLOC = nxt + 2
+        nxt += 3
+        self.KA, self.VA = nxt, nxt + 4           # per-lane LDS addresses of the operand reads in buffer 0
+        nxt += 8
+        self.KSRC = nxt                           # KD registers: global offsets of this wave's K_hat copy pieces
+        self.VSRC = nxt + self.KD                 # VD registers: the same for V
+        self.KSRCC = self.VSRC + self.VD          # KD registers: K_hat pieces of a partial last block (rows clamped)
+        nxt = self.KSRCC + self.KD
+        self.L3, self.ROWLIM = nxt, nxt + 1       # masked bodies: list prefetch of tile u+1; last visible key per lane
+        self.FO = nxt + 2                         # factor O still has to be multiplied by (the reference maximum moved)
+        self.PJ, self.PS = nxt + 3, nxt + 4       # LDS addresses of the list entries of iteration u (blocks, scales)
+        nxt += 5
+        self.O = nxt + (nxt & 1)                  # tuples start at even registers
         self.Q = self.O + 16 * self.NDT
         self.NVGPR = self.Q + 4 * self.NSTEP
+        assert self.NVGPR <= 256
         # ---- SGPRs (pinned) ----
-        names = ("u jpart kb0 kb1 vb0 vb1 ldskd ldsvd ldsjl ldsscl lam2 exec need pv scx scn "
-                 "jk jv r negmagic rt scnn t0 t1 a0 a1 cnt ufull jn execp havefo").split()
+        names = ("u jpart kb0 kb1 vb0 vb1 ldskd ldsvd ldsjl ldsscl lam2 exec pv scx scn jk jv negmagic rt scnn "
+                 "t0 t1 a0 a1 b0 b1 cnt ufull jn mlim ex0 ex1 exp0 exp1 hf0 hf1").split()
         self.sg = {n: 36 + i for i, n in enumerate(names)}
-        assert self.sg["kb0"] % 2 == 0 and self.sg["vb0"] % 2 == 0 and self.sg["a0"] % 2 == 0, self.sg
+        for n in "kb0 vb0 a0 b0 ex0 exp0 hf0".split():
+            assert self.sg[n] % 2 == 0, (n, self.sg)
+
+
+def sp(s, n):
+    """An aligned SGPR pair by the name of its first register."""
+    return f"s[{s[n]}:{s[n] + 1}]"
 
 
 def vr(b, n=1):
     return f"v{b}" if n == 1 else f"v[{b}:{b + n - 1}]"
 
 
-def gen_step(c, o, cur, NST, kbuf, vbuf, masked, pv):
+def gen_step(c, o, cur, NST, kbuf, vbuf, masked, pv, dkbuf, dvbuf, label, late):
     """One iteration body: softmax of S[cur] -> P[cur]; scores of the next tile -> S[1-cur];
     O += P[1-cur] V unless that product was voted out (pv = False: Alg. 1 line 15 said skip); then the
     row maximum of the fresh scores and the two decisions."""
@@ -133,7 +148,7 @@ def gen_step(c, o, cur, NST, kbuf, vbuf, masked, pv):
         # -inf over the scores of keys this lane's row must not see: key offset inside the tile >
         # ROWLIM - 64 j (a tile that does not exist has everything masked); -inf is a negative integer,
         # so the integer maximum below ignores it
-        ops.append((f"v_subrev_u32 v{T1}, s{s['t0']}, v{c.ROWLIM}", 1))
+        ops.append((f"v_subrev_u32 v{T1}, s{s['mlim']}, v{c.ROWLIM}", 1))
         ops.append((f"v_mov_b32 v{T2}, 0xff800000", 1))
         for e in range(32):
             koff = (e >> 4) * 32 + 8 * ((e & 15) >> 2) + (e & 3)
@@ -200,20 +215,15 @@ def gen_step(c, o, cur, NST, kbuf, vbuf, masked, pv):
     o(f"; ---- {'masked' if masked else 'fast'} step: softmax S{cur} -> P{cur} | scores -> S{nxt}"
       + (f", O += P{nxt} V" if pv else " (P~V voted out)"))
     # list entries the next iteration needs (older than every operand read of this step)
-    o(f"s_lshl_b32 s{s['t0']}, s{s['u']}, 1")
-    o(f"s_add_u32 s{s['t0']}, s{s['t0']}, s{s['ldsjl']}")
-    o(f"s_lshl_b32 s{s['t1']}, s{s['u']}, 2")
-    o(f"s_add_u32 s{s['t1']}, s{s['t1']}, s{s['ldsscl']}")
-    o(f"v_mov_b32 v{c.L0}, s{s['t0']}")
-    o(f"v_mov_b32 v{c.L2}, s{s['t1']}")
-    o(f"ds_read_u16 v{c.L1}, v{c.L0} offset:{2 * (NST - 1)}")   # key block of V(u+1+NST-2)
-    o(f"ds_read_u16 v{c.L0}, v{c.L0} offset:{2 * (NST + 1)}")   # key block of K_hat(u+1+NST)
-    o(f"ds_read_b32 v{c.L2}, v{c.L2} offset:8")                 # scale of tile u+2
+    o(f"ds_read_u16 v{c.L1}, v{c.PJ} offset:{2 * (NST - 1)}")   # key block of V(u+1+NST-2)
+    o(f"ds_read_u16 v{c.L0}, v{c.PJ} offset:{2 * (NST + 1)}")   # key block of K_hat(u+1+NST)
+    o(f"ds_read_b32 v{c.L2}, v{c.PS} offset:8")                 # scale of tile u+2
     if masked:
-        o(f"v_mov_b32 v{c.L3}, s{s['t0']}")
-        o(f"ds_read_u16 v{c.L3}, v{c.L3} offset:2")             # key block of tile u+1
+        o(f"ds_read_u16 v{c.L3}, v{c.PJ} offset:2")             # key block of tile u+1
     for sl in range(LA):
         read(sl)
+    o(f"v_add_u32 v{c.PJ}, 2, v{c.PJ}")
+    o(f"v_add_u32 v{c.PS}, 4, v{c.PS}")
     o(f"v_mov_b32 v{c.CX}, s{s['negmagic']}")
     o(f"v_fma_f32 v{c.CX}, v{c.CX}, s{s['scx']}, -v{c.MR}")   # -(bias * scale) - reference maximum
     if masked:  # a row that has not seen a key yet (reference -inf) only has masked scores here
@@ -223,135 +233,98 @@ def gen_step(c, o, cur, NST, kbuf, vbuf, masked, pv):
         o(f"s_add_u32 s{s['pv']}, s{s['pv']}, 1")
     for t in chunks[0]:
         o(t)
+    tag = f"{label}"
     for sl in range(NSLOT):
-        if sl + LA < NSLOT:
-            read(sl + LA)
-        o(f"s_waitcnt lgkmcnt({min(LA, NSLOT - 1 - sl)})")
+        if sl % 2 == 0:
+            issued = min(NSLOT, sl + LA + 2)
+            for t in range(sl + LA, issued):
+                read(t)
+            o(f"s_waitcnt lgkmcnt({issued - (sl + 2)})")      # the operands of this slot and the next have arrived
         mfma(sl)
-        if sl == 0:  # the list entries (older than the operand reads) have arrived
+        ch = list(chunks[sl + 1])
+        if sl == 0:
+            # this wave's pieces of K_hat(jk) and V(jv): group u+NST-1 = {K_hat(u+NST), V(u+NST-2)}.  The
+            # lists are padded with their last entry, so the copies near the end of the list fetch a tile
+            # nobody reads instead of being skipped, and every iteration issues the same number of loads.
+            o(f"s_mul_i32 s{s['t0']}, s{s['jk']}, {c.K_BYTES}")
+            o(f"s_add_u32 s{s['a0']}, s{s['kb0']}, s{s['t0']}")
+            o(f"s_addc_u32 s{s['a1']}, s{s['kb1']}, 0")
+            o(f"s_mul_i32 s{s['t1']}, s{s['jv']}, {c.V_BYTES}")
+            o(f"s_add_u32 s{s['b0']}, s{s['vb0']}, s{s['t1']}")
+            o(f"s_addc_u32 s{s['b1']}, s{s['vb1']}, 0")
+            # the partial last key block is copied with its rows clamped to the last valid one
+            o(f"s_cmp_eq_u32 s{s['jk']}, s{s['jpart']}")
+            o(f"s_cbranch_scc1 L_kclamp{tag}_%=")
+            ins = []
+            for n in range(c.KD):
+                piece = [f"s_add_u32 m0, s{s['ldskd']}, {dkbuf * c.K_BYTES + n * 1024 * NWAVE}", "s_nop 0"]
+                for x in piece:
+                    o(x)
+                o(f"global_load_lds_dwordx4 v{c.KSRC + n}, {sp(s, 'a0')}")
+                ins += piece + [f"global_load_lds_dwordx4 v{c.KSRCC + n}, {sp(s, 'a0')}"]
+            o(f"L_kdone{tag}_%=:")
+            late.append((f"L_kclamp{tag}_%=", ins + [f"s_branch L_kdone{tag}_%="]))
+        if sl == 1:  # the list entries (older than the operand reads) have arrived
             o(f"v_readfirstlane_b32 s{s['jk']}, v{c.L0}")
             o(f"v_readfirstlane_b32 s{s['jv']}, v{c.L1}")
             o(f"v_readfirstlane_b32 s{s['scnn']}, v{c.L2}")
             if masked:
                 o(f"v_readfirstlane_b32 s{s['jn']}, v{c.L3}")
-                o(f"s_lshl_b32 s{s['t0']}, s{s['jn']}, 6")
+                o(f"s_lshl_b32 s{s['mlim']}, s{s['jn']}, 6")
                 o(f"s_add_u32 s{s['t1']}, s{s['u']}, 1")
                 o(f"s_cmp_lt_u32 s{s['t1']}, s{s['cnt']}")
-                o(f"s_cselect_b32 s{s['t0']}, s{s['t0']}, 0x40000000")   # no tile u+1: mask everything
-                o(f"s_cselect_b32 s{s['scn']}, s{s['scn']}, 1.0")        # and do not use a scale from past the list
-        for t in chunks[sl + 1]:
+                o(f"s_cselect_b32 s{s['mlim']}, s{s['mlim']}, 0x40000000")   # no tile u+1: mask everything
+                o(f"s_cselect_b32 s{s['scn']}, s{s['scn']}, 1.0")            # and do not use a scale from past the list
+        if 2 <= sl < 2 + c.VD:
+            # one V piece per slot; the vector instruction between the M0 write and the copy is the wait
+            # state that write needs
+            n = sl - 2
+            o(f"s_add_u32 m0, s{s['ldsvd']}, {dvbuf * c.V_BYTES + n * 1024 * NWAVE}")
+            o(ch.pop(0) if ch else "s_nop 0")
+            o(f"global_load_lds_dwordx4 v{c.VSRC + n}, {sp(s, 'b0')}")
+        for t in ch:
             o(t)
-    # stage-2 decision of the new tile; has the maximum run away from the reference?
-    o(f"s_mov_b32 s{s['execp']}, s{s['exec']}")   # the tile whose P~ was just made keeps its decision
-    o(f"v_cmp_lt_f32 vcc, s{s['lam2']}, v{T0}")
-    o("s_cmp_lg_u64 vcc, 0")
-    o(f"s_cselect_b32 s{s['exec']}, 1, 0")
+    assert NSLOT >= 2 + c.VD
+    # stage-2 decision of the new tile (kept as a lane mask); has the maximum run away from the reference?
+    o(f"s_mov_b64 {sp(s, 'exp0')}, {sp(s, 'ex0')}")   # the tile whose P~ was just made keeps its decision
+    o(f"v_cmp_lt_f32_e64 {sp(s, 'ex0')}, s{s['lam2']}, v{T0}")
     o(f"v_cmp_lt_f32 vcc, s{s['rt']}, v{T1}")
-    o("s_cmp_lg_u64 vcc, 0")
-    o(f"s_cselect_b32 s{s['need']}, 1, 0")
     o(f"s_add_u32 s{s['u']}, s{s['u']}, 1")
     o(f"s_mov_b32 s{s['scx']}, s{s['scn']}")
     o(f"s_mov_b32 s{s['scn']}, s{s['scnn']}")
-
-
-def gen_top(c, o, NST, dkbuf, dvbuf, r, late):
-    r = f"{r}"  # label suffix (fast and masked bodies have their own)
-    """Top of an iteration: wait, barrier, the wave's share of the next tile copies.  Copies are issued
-    in groups {K_hat(t+1), V(t-1)}, group u+NST-1 here; near the end of the list a group shrinks."""
-    s = c.sg
-    if NST == 3:
-        # younger than the group this iteration needs: group u+1 = {K_hat(u+2), V(u)}
-        o(f"s_add_u32 s{s['t0']}, s{s['u']}, 2")
-        o(f"s_cmp_lt_u32 s{s['t0']}, s{s['cnt']}")
-        o(f"s_cbranch_scc0 L_tailw{r}_%=")
-        o(f"s_waitcnt vmcnt({c.NDMA})")
-        o(f"L_waited{r}_%=:")
-        late.append((f"L_tailw{r}_%=", [f"s_cmp_lt_u32 s{s['u']}, s{s['cnt']}",
-                                         f"s_cbranch_scc0 L_tailw0_{r}_%=",
-                                         f"s_waitcnt vmcnt({c.VD})", f"s_branch L_waited{r}_%=",
-                                         f"L_tailw0_{r}_%=:", "s_waitcnt vmcnt(0)", f"s_branch L_waited{r}_%="]))
-    else:
-        assert NST == 2
-        o("s_waitcnt vmcnt(0)")
-    o("s_barrier")
-    # LDS-DMA: this wave's pieces of K_hat(jk) and V(jv)
-    o(f"s_add_u32 s{s['t0']}, s{s['u']}, {NST}")
-    o(f"s_cmp_lt_u32 s{s['t0']}, s{s['cnt']}")
-    o(f"s_cbranch_scc0 L_skipk{r}_%=")
-    o(f"s_mul_i32 s{s['t0']}, s{s['jk']}, {c.K_BYTES}")
-    o(f"s_add_u32 s{s['a0']}, s{s['kb0']}, s{s['t0']}")
-    o(f"s_addc_u32 s{s['a1']}, s{s['kb1']}, 0")
-    # the partial last key block is copied with its rows clamped to the last valid one
-    o(f"s_cmp_eq_u32 s{s['jk']}, s{s['jpart']}")
-    o(f"s_cbranch_scc1 L_kclamp{r}_%=")
-    ins = []
-    for n in range(c.KD):
-        ins += [f"s_add_u32 m0, s{s['ldskd']}, {dkbuf * c.K_BYTES + n * 1024 * NWAVE}", "s_nop 0",
-                f"global_load_lds_dwordx4 v{c.KSRCC + n}, s[{s['a0']}:{s['a1']}]"]
-    late.append((f"L_kclamp{r}_%=", ins + [f"s_branch L_skipk{r}_%="]))
-    for n in range(c.KD):
-        if n:  # the wave's next piece lies 4 KB further on both sides
-            o(f"s_add_u32 s{s['a0']}, s{s['a0']}, {1024 * NWAVE}")
-            o(f"s_addc_u32 s{s['a1']}, s{s['a1']}, 0")
-        o(f"s_add_u32 m0, s{s['ldskd']}, {dkbuf * c.K_BYTES + n * 1024 * NWAVE}")
-        o("s_nop 0")
-        o(f"global_load_lds_dwordx4 v{c.KSRC}, s[{s['a0']}:{s['a1']}]")
-    o(f"L_skipk{r}_%=:")
-    o(f"s_add_u32 s{s['t0']}, s{s['u']}, {NST - 2}")
-    o(f"s_cmp_lt_u32 s{s['t0']}, s{s['cnt']}")
-    o(f"s_cbranch_scc0 L_skipv{r}_%=")
-    o(f"s_mul_i32 s{s['t0']}, s{s['jv']}, {c.V_BYTES}")
-    o(f"s_add_u32 s{s['a0']}, s{s['vb0']}, s{s['t0']}")
-    o(f"s_addc_u32 s{s['a1']}, s{s['vb1']}, 0")
-    for n in range(c.VD):
-        if n:
-            o(f"s_add_u32 s{s['a0']}, s{s['a0']}, {1024 * NWAVE}")
-            o(f"s_addc_u32 s{s['a1']}, s{s['a1']}, 0")
-        o(f"s_add_u32 m0, s{s['ldsvd']}, {dvbuf * c.V_BYTES + n * 1024 * NWAVE}")
-        o("s_nop 0")
-        o(f"global_load_lds_dwordx4 v{c.VSRC}, s[{s['a0']}:{s['a1']}]")
-    o(f"L_skipv{r}_%=:")
-
-
-def gen_moves(c, o, tag, late):
-    """After a step: O *= fO if a move of the reference maximum is still owed to O (the P~V product that
-    was pending when the reference moved has now been added), then the move the step just asked for:
-    l and m_ref at once, O one iteration later.  Both are rare and live out of line."""
-    s = c.sg
-    T0 = c.T
-    o(f"s_cmp_lg_u32 s{s['havefo']}, 0")
-    o(f"s_cbranch_scc1 L_applyfo{tag}_%=")
-    o(f"L_afterfo{tag}_%=:")
-    o(f"s_cmp_lg_u32 s{s['need']}, 0")
-    o(f"s_cbranch_scc1 L_move{tag}_%=")
-    o(f"L_aftermove{tag}_%=:")
-    ins = ["s_nop 7", "s_nop 7", "s_nop 7"]    # the step's last MFMA results have landed
+    # Rare, out of line: O *= fO if a move of the reference maximum is still owed to O (the P~V product
+    # that was pending when the reference moved has now been added), then the move this step asks for:
+    # l and m_ref at once, O one iteration later.
+    o(f"s_or_b64 vcc, vcc, {sp(s, 'hf0')}")
+    o(f"s_cbranch_scc1 L_slow{tag}_%=")
+    o(f"L_after{tag}_%=:")
+    ins = [f"s_cmp_eq_u64 {sp(s, 'hf0')}, 0",
+           f"s_cbranch_scc1 L_slowb{tag}_%=",
+           "s_nop 7", "s_nop 7", "s_nop 7"]               # the step's last MFMA results have landed
     ins += [f"v_mul_f32 v{c.O + i}, v{c.O + i}, v{c.FO}" for i in range(16 * c.NDT)]
-    ins += [f"s_mov_b32 s{s['havefo']}, 0", "s_nop 3", f"s_branch L_afterfo{tag}_%="]
-    late.append((f"L_applyfo{tag}_%=", ins))
-    ins = [f"v_sub_f32 v{T0}, v{c.MR}, v{c.MT}",
-           f"v_exp_f32 v{T0}, v{T0}",
-           f"v_mov_b32 v{c.MR}, v{c.MT}",
-           "s_nop 0",
-           f"v_mul_f32 v{c.L}, v{c.L}, v{T0}",
-           f"v_mov_b32 v{c.FO}, v{T0}",
-           f"s_mov_b32 s{s['havefo']}, 1",
-           f"s_mov_b32 s{s['need']}, 0",
-           f"s_branch L_aftermove{tag}_%="]
-    late.append((f"L_move{tag}_%=", ins))
+    ins += [f"s_mov_b64 {sp(s, 'hf0')}, 0",
+            f"L_slowb{tag}_%=:",
+            f"v_cmp_lt_f32 vcc, s{s['rt']}, v{T1}",
+            "s_cmp_eq_u64 vcc, 0",
+            f"s_cbranch_scc1 L_after{tag}_%=",
+            f"v_sub_f32 v{T0}, v{c.MR}, v{c.MT}",
+            f"v_exp_f32 v{T0}, v{T0}",
+            f"v_mov_b32 v{c.MR}, v{c.MT}",
+            "s_nop 0",
+            f"v_mul_f32 v{c.L}, v{c.L}, v{T0}",
+            f"v_mov_b32 v{c.FO}, v{T0}",
+            f"s_mov_b64 {sp(s, 'hf0')}, -1",
+            "s_nop 3",
+            f"s_branch L_after{tag}_%="]
+    late.append((f"L_slow{tag}_%=", ins))
 
 
-def gen_go(c, o, r):
-    """Which body runs iteration u = r (mod period), if any.  u has been counted up already."""
-    s = c.sg
-    o(f"L_go{r}_%=:")
-    o(f"s_cmp_ge_u32 s{s['u']}, s{s['cnt']}")
-    o(f"s_cbranch_scc1 L_drain{r}_%=")
-    o(f"s_add_u32 s{s['t0']}, s{s['u']}, 1")
-    o(f"s_cmp_lt_u32 s{s['t0']}, s{s['ufull']}")
-    o(f"s_cbranch_scc0 L_tomask{r}_%=")
-    o(f"s_cmp_eq_u32 s{s['execp']}, 0")
-    o(f"s_cbranch_scc1 L_fastnopv{r}_%=")
+def gen_top(c, o, NST):
+    """Top of an iteration: the wave's own copy pieces of the group this iteration reads (everything but
+    the NST-2 youngest groups) have landed; the barrier makes every wave's pieces visible and frees the
+    buffers the previous iteration read."""
+    o(f"s_waitcnt vmcnt({c.NDMA * (NST - 2)})")
+    o("s_barrier")
 
 
 def gen_loop(c, NST):
@@ -361,21 +334,30 @@ def gen_loop(c, NST):
     period = 2 * NST if NST % 2 else NST  # bodies: one set per value of u mod lcm(2, NST)
     o(f"s_mov_b32 s{s['negmagic']}, 0x{MAGIC_NEG:08x}")
     o(f"s_mov_b32 s{s['rt']}, 0x{RESCALE_T:08x}")
+    o(f"s_cmp_lg_u32 s{s['exec']}, 0")                 # stage-2 decision of tile 0 as a lane mask
+    o(f"s_cselect_b64 {sp(s, 'ex0')}, -1, 0")
+    o(f"s_mov_b64 {sp(s, 'exp0')}, 0")                 # nothing is pending: iteration 0 has no P~V
+    o(f"s_mov_b64 {sp(s, 'hf0')}, 0")
+    o(f"v_mov_b32 v{c.PJ}, s{s['ldsjl']}")
+    o(f"v_mov_b32 v{c.PS}, s{s['ldsscl']}")
     o("s_waitcnt vmcnt(0) lgkmcnt(0)")
-    for r in range(1, period):
-        o(f"s_cmp_eq_u32 s{s['r']}, {r}")
-        o(f"s_cbranch_scc1 L_go{r}_%=")
     late = []  # out-of-line pieces: (label, instructions)
 
-    def body(r, masked, pv, tag):
+    def body(r, masked, pv, kind):
         # iteration u = r (mod period): K_hat(u+1) in buffer (u+1) % NST, V(u-1) in (u-1) % NST;
         # the new copies go to u % NST (K_hat) and (u-2) % NST (V)
-        gen_top(c, o, NST, r % NST, (r - 2) % NST, f"{tag}{r}", late)
-        gen_step(c, o, r & 1, NST, (r + 1) % NST, (r - 1) % NST, masked, pv)
-        gen_moves(c, o, f"{tag}{r}", late)
+        gen_top(c, o, NST)
+        gen_step(c, o, r & 1, NST, (r + 1) % NST, (r - 1) % NST, masked, pv, r % NST, (r - 2) % NST,
+                 f"{kind}{r}", late)
 
     for r in range(period):
-        gen_go(c, o, r)
+        # which body runs iteration u = r (mod period), if any; u has been counted up already
+        o(f"L_go{r}_%=:")
+        o(f"s_add_u32 s{s['t0']}, s{s['u']}, 1")
+        o(f"s_cmp_lt_u32 s{s['t0']}, s{s['ufull']}")
+        o(f"s_cbranch_scc0 L_tomask{r}_%=")
+        o(f"s_cmp_eq_u64 {sp(s, 'exp0')}, 0")
+        o(f"s_cbranch_scc1 L_fastnopv{r}_%=")
         body(r, False, True, "f")
         if r == period - 1:
             o("s_branch L_go0_%=")
@@ -384,14 +366,16 @@ def gen_loop(c, NST):
         o(f"L_fastnopv{r}_%=:")
         body(r, False, False, "g")
         o(nxt)
+        o(f"L_tomask{r}_%=:")
+        o(f"s_cmp_ge_u32 s{s['u']}, s{s['cnt']}")
+        o(f"s_cbranch_scc0 L_tomaskb{r}_%=")
         # the drain (u = cnt) runs the pending P~V of the last tile if it was voted in; then the block is done
-        o(f"L_drain{r}_%=:")
         o(f"s_cmp_eq_u32 s{s['u']}, s{s['cnt']}")
         o("s_cbranch_scc0 L_exit_%=")
-        o(f"s_cmp_eq_u32 s{s['execp']}, 0")
+        o(f"s_cmp_eq_u64 {sp(s, 'exp0')}, 0")
         o("s_cbranch_scc1 L_exit_%=")
-        o(f"L_tomask{r}_%=:")
-        o(f"s_cmp_eq_u32 s{s['execp']}, 0")
+        o(f"L_tomaskb{r}_%=:")
+        o(f"s_cmp_eq_u64 {sp(s, 'exp0')}, 0")
         o(f"s_cbranch_scc1 L_masknopv{r}_%=")
         body(r, True, True, "m")
         o(nxt)
@@ -403,13 +387,14 @@ def gen_loop(c, NST):
         for i in ins:
             o(i)
     o("L_exit_%=:")
+    o("s_waitcnt vmcnt(0)")                    # no copy of this wave may still be writing LDS
     o("s_nop 7"); o("s_nop 7"); o("s_nop 7")   # the last MFMA results have landed
     return lines
 
 
 def clobbers(c):
-    v = list(range(c.RG, c.RG + 16)) + list(range(c.T, c.T + 3)) + [c.CX, c.L3]
-    sg = [c.sg[n] for n in "negmagic rt scnn t0 t1 a0 a1 jn".split()]
+    v = list(range(c.RG, c.RG + 4 * RING)) + list(range(c.T, c.T + 3)) + [c.CX, c.L3, c.PJ, c.PS]
+    sg = [c.sg[n] for n in ("negmagic rt scnn t0 t1 a0 a1 b0 b1 jn mlim ex0 ex1 exp0 exp1 hf0 hf1").split()]
     return [f"v{i}" for i in v] + [f"s{i}" for i in sg] + ["vcc", "scc", "memory"]
 
 
@@ -417,14 +402,18 @@ def gen_function(c, NST):
     s = c.sg
     body = gen_loop(c, NST)
     dtn = "SPARGE_BF16" if c.dt == "bf16" else "SPARGE_F16"
+    io_names = "u jk jv scn scx pv".split()                       # read and written by the block
+    in_names = "exec jpart cnt ufull ldskd ldsvd ldsjl ldsscl lam2".split()
+    floats = {"scn", "scx", "lam2"}
     out = []
     w = out.append
     w(f"// head dimension {c.D}, {c.dt}, {NST} LDS stages: {c.NVGPR} VGPRs pinned, no AGPRs")
     w(f"template <> struct FastLoop<{c.D}, {dtn}, {NST}> {{")
     w("    template <class St>")
     w("    static __device__ __forceinline__ void run(St& w, const v16i& magic, FastLoopArgs& p) {")
-    for n in "u jk jv scn scx exec execp need havefo pv r jpart cnt ufull ldskd ldsvd ldsjl ldsscl lam2".split():
-        if n in ("scn", "scx", "lam2"):
+    # scalar operands go through readfirstlane copies: the register allocator then knows they are uniform
+    for n in io_names + in_names:
+        if n in floats:
             w(f"        float {n}_ = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(p.{n})));")
         else:
             w(f"        int {n}_ = __builtin_amdgcn_readfirstlane(static_cast<int>(p.{n}));")
@@ -442,10 +431,6 @@ def gen_function(c, NST):
     for reg, expr in ((c.MT, "w.m_true"), (c.MR, "w.m_ref"), (c.L, "w.l")):
         outs.append(f'"+{{v{reg}}}"({expr})')
     outs.append(f'"+{{v{c.FO}}}"(p.fo)')
-    # scalar operands go through readfirstlane copies: the register allocator then knows they are uniform
-    io_names = "u jk jv scn scx exec execp need havefo pv".split()
-    in_names = "r jpart cnt ufull ldskd ldsvd ldsjl ldsscl lam2".split()
-    floats = {"scn", "scx", "lam2"}
     for n in io_names:
         outs.append(f'"+{{s{s[n]}}}"({n}_)')
     for st in range(c.NSTEP):
@@ -457,18 +442,19 @@ def gen_function(c, NST):
         ins.append(f'"{{v{c.KA + st}}}"(p.k_adr[{st}])')
     for ks in range(4):
         ins.append(f'"{{v{c.VA + ks}}}"(p.v_adr[{ks}])')
-    ins.append(f'"{{v{c.KSRC}}}"(p.k_src)')
     for n in range(c.KD):
+        ins.append(f'"{{v{c.KSRC + n}}}"(p.k_src[{n}])')
         ins.append(f'"{{v{c.KSRCC + n}}}"(p.k_src_clamped[{n}])')
-    ins.append(f'"{{v{c.VSRC}}}"(p.v_src)')
-    ins.append(f'"{{s[{s["kb0"]}:{s["kb1"]}]}}"(p.kbase)')
-    ins.append(f'"{{s[{s["vb0"]}:{s["vb1"]}]}}"(p.vbase)')
+    for n in range(c.VD):
+        ins.append(f'"{{v{c.VSRC + n}}}"(p.v_src[{n}])')
+    ins.append(f'"{{{sp(s, "kb0")}}}"(p.kbase)')
+    ins.append(f'"{{{sp(s, "vb0")}}}"(p.vbase)')
     for n in in_names:
         ins.append(f'"{{s{s[n]}}}"({n}_)')
     w("            : " + ",\n              ".join(outs))
     w("            : " + ",\n              ".join(ins))
     w("            : " + ", ".join(f'"{x}"' for x in clobbers(c)) + ");")
-    for n in "u jk jv scn scx exec execp need havefo pv".split():
+    for n in ("u", "pv"):
         w(f"        p.{n} = {n}_;")
     w("    }")
     w("};")
