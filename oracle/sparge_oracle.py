@@ -34,6 +34,14 @@ Readings of the paper where it is silent or ambiguous (each also listed in the d
     maximum itself at every tile (the recurrence exactly as printed); ref_slack > 0 lets it lag:
     before a tile's softmax, if some row of a 32-row group has m - m_ref > ref_slack, the whole
     group's reference moves to the running maximum.  Only the rounding of P~ can tell the difference.
+  * FP8 P~V (the paper only credits a SageAttention2-based kernel with it, footnote of Sec. 1; no
+    formulas): pv_dtype = "fp8e4m3".  V is quantized per (head, channel) over all tokens to OCP E4M3
+    (1-4-3 bits, bias 7, subnormals, largest finite value 448, round to nearest even):
+    delta_V[c] = fp32(max_t |V[t,c]|) / 448 in fp32, V-hat = e4m3(fp32(V[t,c]) / delta_V[c]), a zero
+    channel gives 0.  P~ is scaled by c_P = 448 * exp(-ref_slack) -- the largest value the lagging
+    reference lets it take, mapped onto the largest E4M3 value -- and rounded to E4M3; products are
+    exact and accumulate in fp64 here (fp32 on the GPU); O = (sum P~_q V-hat) * delta_V / (c_P * l), l
+    from the unrounded P~ as always.
 """
 from __future__ import annotations
 
@@ -268,6 +276,55 @@ def round16(x: np.ndarray, dtype: str) -> np.ndarray:
     raise ValueError(dtype)
 
 
+E4M3_MAX = 448.0
+
+
+def round_e4m3(x: np.ndarray) -> np.ndarray:
+    """Round to the nearest OCP FP8 E4M3 value (ties to even), returned as fp64.
+
+    E4M3: 1 sign, 4 exponent (bias 7), 3 mantissa bits; normal values 2^e (1 + m/8), e in [-6, 8],
+    the code with all exponent and mantissa bits set is NaN, so the largest finite value is 448;
+    subnormals m/8 * 2^-6.  Inside one binade the values are multiples of 2^(e-3): rounding the
+    multiple to the nearest integer, ties to even, is round-to-nearest-even on the mantissa.
+    Inputs must not round past 448 (the format has no infinity; the method never produces them).
+    """
+    x = np.asarray(x, dtype=np.float64)
+    a = np.abs(x)
+    with np.errstate(divide="ignore"):
+        e = np.floor(np.log2(np.where(a > 0, a, 1.0)))
+    e = np.clip(e, -6, 8)
+    step = np.exp2(e - 3)
+    r = np.rint(a / step) * step
+    if np.any(r > E4M3_MAX):
+        raise ValueError("value rounds past the largest finite E4M3 number")
+    return np.copysign(r, x)
+
+
+def encode_e4m3(x: np.ndarray) -> np.ndarray:
+    """The byte codes (sign << 7 | exponent << 3 | mantissa) of round_e4m3(x)."""
+    r = round_e4m3(x)
+    a = np.abs(r)
+    with np.errstate(divide="ignore"):
+        e = np.floor(np.log2(np.where(a > 0, a, 1.0)))
+    normal = a >= 2.0 ** -6
+    E = np.where(normal, e + 7, 0).astype(np.int64)
+    M = np.where(normal, np.rint((a / np.exp2(e) - 1.0) * 8), np.rint(a * 2.0 ** 9)).astype(np.int64)
+    sign = (np.signbit(r)).astype(np.int64)
+    return ((sign << 7) | (E << 3) | M).astype(np.uint8)
+
+
+def quantize_v_fp8(V: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """Per-channel E4M3 quantization of one head's V [N, d]: (V-hat as fp64 grid values, delta_V fp32 [d]).
+    The division runs in fp32, as stated in the module header."""
+    V32 = np.asarray(V, dtype=np.float32)
+    amax = np.abs(V32).max(axis=0)
+    delta = (amax / np.float32(E4M3_MAX)).astype(np.float32)
+    safe = np.where(delta > 0, delta, np.float32(1.0)).astype(np.float32)
+    scaled = (V32 / safe[None, :]).astype(np.float32)
+    Vq = round_e4m3(np.where(delta[None, :] > 0, scaled, np.float32(0.0)).astype(np.float64))
+    return Vq, delta
+
+
 # ----------------------------------------------------------------------------------------------
 # Stage 2: sparse flash loop with the lambda skip (Alg. 1 lines 7-20; Sec. 3.1, 3.3, 3.4)
 # ----------------------------------------------------------------------------------------------
@@ -298,7 +355,8 @@ def sparse_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, mask: Optional
     quant=True: S_ij = (Q-hat_i K-hat_j^T, exact integers) * delta_Q[i] * delta_K[j] * scale with the
     quantizers above (K smoothed).  quant=False: S_ij = scale * Q_i K_j^T in fp64.
     pv_dtype: "fp16"/"bf16" rounds P~ to that type before the P~V product (the 16-bit matrix
-    unit's input); the row sum l always uses the unrounded P~.  mask=None means all ones.
+    unit's input); "fp8e4m3" is the FP8 product described in the module header; the row sum l always
+    uses the unrounded P~.  mask=None means all ones.
     ref_slack (natural-log units): how far the running maximum may run ahead of the reference that
     exp subtracts (see the module header); 0 = the recurrence of Alg. 1 lines 12-16 as printed.
     """
@@ -314,6 +372,10 @@ def sparse_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, mask: Optional
         Kh, dK, _ = quantize_k(K)
         Qh = Qh.astype(np.float64)
         Kh = Kh.astype(np.float64)
+    fp8 = pv_dtype == "fp8e4m3"
+    if fp8:
+        V, delta_V = quantize_v_fp8(V)           # from here on V holds V-hat
+        c_P = E4M3_MAX * math.exp(-ref_slack)
     O = np.zeros((N, d), dtype=np.float64)
     qk_tiles = pv_groups = valid_tiles = valid_groups = zero_rows = 0
     for i in (range(Tm) if q_blocks is None else q_blocks):
@@ -364,7 +426,7 @@ def sparse_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, mask: Optional
             m_safe = np.where(live, m_ref, 0.0)
             P = np.exp(S - m_safe[:, None])          # exp(-inf) = 0 for masked entries
             l = l + P.sum(axis=1)
-            Pr = round16(P, pv_dtype)
+            Pr = round_e4m3(P * c_P) if fp8 else round16(P, pv_dtype)
             for g0 in range(0, nr, ROW_GROUP):
                 g1 = min(g0 + ROW_GROUP, nr)
                 with np.errstate(invalid="ignore"):
@@ -378,6 +440,8 @@ def sparse_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, mask: Optional
             m = m_new
         dead = l == 0
         zero_rows += int(dead.sum())
+        if fp8:
+            Oi = Oi * delta_V.astype(np.float64)[None, :] / c_P
         O[r0:r1] = np.where(dead[:, None], 0.0, Oi / np.where(dead, 1.0, l)[:, None])
     return AttnResult(O, qk_tiles, pv_groups, valid_tiles, valid_groups, zero_rows)
 

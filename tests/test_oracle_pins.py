@@ -574,3 +574,88 @@ def test_reference_moves_per_row_group_when_one_row_runs_ahead():
         l = np.exp(S[row, :64] - m0).sum() * np.exp(m0 - ref1) + np.exp(S[row, 64:] - ref1).sum()
         want = (p0 @ V[:64, 0] + p1 @ V[64:, 0]) / l
         assert abs(r.O[row, 0] - want) < 1e-12, (row, r.O[row, 0], want)
+
+
+# ------------------------------------------------------------------ FP8 (E4M3) P~V product
+def _e4m3_values():
+    """All non-negative finite E4M3 numbers, written out from the format definition."""
+    vals = [m / 8.0 * 2.0 ** -6 for m in range(8)]                                   # zero and subnormals
+    vals += [2.0 ** (E - 7) * (1 + m / 8.0) for E in range(1, 16) for m in range(8)]  # normals
+    return np.array(vals[:-1])                                                       # S.1111.111 is NaN
+
+
+def test_e4m3_grid_nearest_even_and_library_conversion():
+    torch = pytest.importorskip("torch")
+    g = _e4m3_values()
+    assert g.size == 127 and g.max() == 448.0 and g[1] == 2.0 ** -9
+    np.testing.assert_array_equal(so.round_e4m3(g), g)                 # idempotent on the grid
+    np.testing.assert_array_equal(so.round_e4m3(-g), -g)
+    np.testing.assert_array_equal(so.encode_e4m3(g), np.arange(127, dtype=np.uint8))
+    np.testing.assert_array_equal(so.encode_e4m3(-g[1:]), np.arange(1, 127, dtype=np.uint8) | 0x80)
+    # nearest grid value for random fp32 inputs, by brute force over the grid
+    x = rng(70).uniform(-448, 448, 20000).astype(np.float32).astype(np.float64)
+    x = np.concatenate([x, rng(71).uniform(-0.04, 0.04, 20000).astype(np.float32).astype(np.float64)])
+    r = so.round_e4m3(x)
+    full = np.concatenate([-g[::-1], g])
+    best = np.abs(x[:, None] - full[None, :]).min(axis=1)
+    np.testing.assert_array_equal(np.abs(r - x), best)
+    # ties go to the even mantissa: midpoints of neighbouring grid values
+    mid = (g[:-1] + g[1:]) / 2
+    even = np.where(np.arange(126) % 2 == 0, g[:-1], g[1:])
+    np.testing.assert_array_equal(so.round_e4m3(mid), even)
+    assert so.round_e4m3(np.array([1.0625]))[0] == 1.0 and so.round_e4m3(np.array([1.1875]))[0] == 1.25
+    assert so.round_e4m3(np.array([2.0 ** -10]))[0] == 0.0 and so.round_e4m3(np.array([0.00098]))[0] == 2.0 ** -9
+    with pytest.raises(ValueError):
+        so.round_e4m3(np.array([480.0]))
+    # the library's conversion (fp32 -> float8_e4m3fn) agrees on fp32 inputs
+    t = torch.tensor(x, dtype=torch.float32).to(torch.float8_e4m3fn)
+    np.testing.assert_array_equal(t.to(torch.float64).numpy(), r)
+    np.testing.assert_array_equal(t.view(torch.uint8).numpy(), so.encode_e4m3(x))
+
+
+def test_fp8_v_quantization_per_channel():
+    r = rng(72)
+    V = as16(r.standard_normal((300, 16)) * r.uniform(0.01, 30, 16)[None, :])
+    V[:, 3] = 0.0
+    Vq, delta = so.quantize_v_fp8(V)
+    amax = np.abs(V).max(axis=0)
+    np.testing.assert_allclose(delta, amax / 448.0, rtol=2e-7)
+    assert delta[3] == 0 and np.all(Vq[:, 3] == 0)
+    assert np.abs(Vq).max() == 448.0 and np.all(np.abs(Vq).max(axis=0)[delta > 0] == 448.0)
+    # dequantized values lie within half an E4M3 step (2^-4 relative, 2^-10 of the range near zero) of V
+    err = np.abs(Vq * delta[None, :] - V)
+    assert np.all(err <= np.maximum(np.abs(V) * 2.0 ** -4, amax[None, :] / 448 * 2.0 ** -10) * (1 + 1e-6))
+
+
+def test_fp8_product_exact_when_operands_sit_on_the_grid():
+    # one-hot attention (each query sees one key overwhelmingly) with V on a per-channel E4M3 grid:
+    # P~ is 1 at one key, c_P = 448 e^{-slack} = 112 is an E4M3 number, so O must equal that V row
+    N, d = 256, 64
+    g = _e4m3_values()
+    r = rng(73)
+    ch_scale = 2.0 ** r.integers(-3, 4, d)
+    V = r.choice(g[40:], (N, d)) * r.choice([-1.0, 1.0], (N, d))
+    V[0] = 448.0                                  # every channel's amax is 448 -> delta = its scale
+    V = V * ch_scale[None, :]
+    Q = np.zeros((N, d)); K = np.zeros((N, d))
+    dirs = r.standard_normal((N, d)); dirs /= np.linalg.norm(dirs, axis=1, keepdims=True)
+    Q[:] = dirs * 300.0; K[:] = dirs            # q_t . k_t = 300, q_t . k_s ~ N(0, 300^2/d): far below
+    res = so.sparse_attention(Q, K, V, None, quant=False, pv_dtype="fp8e4m3", ref_slack=2 * math.log(2.0),
+                              scale=1.0)
+    exact = so.dense_attention(Q, K, V, scale=1.0)
+    assert so.rel_l1(exact, V) < 1e-12          # the construction is one-hot
+    np.testing.assert_allclose(res.O, V, rtol=1e-12, atol=0)
+
+
+def test_fp8_product_error_is_a_few_percent_and_above_the_16_bit_one():
+    Q, K, V = _peaky_inputs(74, N=512)
+    exact = so.sparse_attention(Q, K, V, None, quant=False, pv_dtype="none").O
+    e8 = so.rel_l1(so.sparse_attention(Q, K, V, None, quant=False, pv_dtype="fp8e4m3",
+                                       ref_slack=2 * math.log(2.0)).O, exact)
+    e16 = so.rel_l1(so.sparse_attention(Q, K, V, None, quant=False, pv_dtype="bf16").O, exact)
+    # two roundings with unit roundoff 2^-4 per product, averaged over the keys a row attends to
+    assert e16 < e8 < 2 * 2.0 ** -4
+    # with V = 1 in every channel, V-hat = 448 exactly and only the rounding of P~ is left
+    ones = so.sparse_attention(Q, K, np.ones_like(V), None, quant=False, pv_dtype="fp8e4m3",
+                               ref_slack=2 * math.log(2.0)).O
+    assert 0 < np.abs(ones - 1.0).max() < 2.0 ** -4
