@@ -26,6 +26,7 @@ sys.path.insert(0, ROOT)
 
 PEAK_INT8 = 5.0e15   # MI355X dense INT8 MFMA, op/s
 PEAK_16 = 2.5e15     # MI355X dense fp16/bf16 MFMA, flop/s
+PEAK_FP8 = 5.0e15    # MI355X dense FP8 MFMA, flop/s
 PEAK_HBM = 8.0e12    # B/s
 # HBM-side bytes per launch of the attention kernel (read + written), from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs of this script scaled by a 1 GiB copy (profiles/attn_kernel_hbm_traffic.txt).  They belong
@@ -86,21 +87,21 @@ def event_time(fn, reps=5, warmup=2):
     return float(np.median(out))
 
 
-def run_workload(w, data, steps, warmup, detail=True):
+def run_workload(w, data, steps, warmup, detail=True, pv_fp8=False):
     import torch
     import paper_2502_18137_amd as sp
 
     Q, K, V = (sp.tensor_from_numpy(data[t], w.dtype) for t in "qkv")
-    ws = torch.empty(sp.sparge_workspace_bytes(Q, sp.WS_FORWARD), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(sp.sparge_workspace_bytes(Q, sp.WS_FORWARD, pv_fp8), dtype=torch.uint8, device="cuda")
     O = torch.empty_like(V)
     mask = torch.empty((w.B, w.H, (w.N + 127) // 128, (w.N + 63) // 64), dtype=torch.uint8, device="cuda")
 
     def step():
-        sp.sparge_forward(Q, K, V, w.tau, w.theta, w.lam, causal=w.causal, ws=ws, out=O)
+        sp.sparge_forward(Q, K, V, w.tau, w.theta, w.lam, causal=w.causal, ws=ws, out=O, pv_fp8=pv_fp8)
 
     # one instrumented pass for the counters and the mask
     _, mask, stats = sp.sparge_forward(Q, K, V, w.tau, w.theta, w.lam, causal=w.causal, ws=ws, out=O,
-                                       return_mask=True, return_stats=True)
+                                       return_mask=True, return_stats=True, pv_fp8=pv_fp8)
     torch.cuda.synchronize()
     stats = stats.cpu().numpy()
 
@@ -119,7 +120,7 @@ def run_workload(w, data, steps, warmup, detail=True):
     attn_ms = float(np.mean(attn_ms_list))
 
     qk_ops, pv_flops = executed_ops(stats, w.d)
-    ideal_s = qk_ops / PEAK_INT8 + pv_flops / PEAK_16
+    ideal_s = qk_ops / PEAK_INT8 + pv_flops / (PEAK_FP8 if pv_fp8 else PEAK_16)
     total = qk_ops + pv_flops
     res = {
         "ms_per_step": ms_step,
@@ -134,12 +135,12 @@ def run_workload(w, data, steps, warmup, detail=True):
             "peak": total / ideal_s / 1e12,
             "unit": "TFLOP/s",
             "frac": ideal_s / (attn_ms * 1e-3),
-            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if w.H == CONFIGS_H.get(w.name) else None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if w.H == CONFIGS_H.get(w.name) and not pv_fp8 else None,
             "traffic_unit": "bytes per launch (HBM side of L2, rocprofv3 FETCH_SIZE + WRITE_SIZE)",
             "executed_int8_ops": qk_ops, "executed_16bit_flops": pv_flops,
         },
     }
-    if detail:
+    if detail and not pv_fp8:
         wsq = torch.empty(sp.sparge_workspace_bytes(Q, sp.WS_QUANTIZE), dtype=torch.uint8, device="cuda")
         wsp = torch.empty(sp.sparge_workspace_bytes(Q, sp.WS_PREDICT), dtype=torch.uint8, device="cuda")
         res["quantize_ms"] = event_time(lambda: sp.sparge_quantize(Q, K, ws=wsq))
@@ -267,6 +268,7 @@ def main():
     ap.add_argument("--no-also", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-detail", action="store_true")
+    ap.add_argument("--no-fp8", action="store_true", help="skip the FP8 P~V variant of each workload")
     ap.add_argument("--heads", type=int, default=0, help="debug: fewer heads (result is then not the headline)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy, the known-size dispatch that HBM counter "
@@ -294,7 +296,7 @@ def main():
         del src, dst
     names = [args.workload] + ([] if args.no_also else [n for n in args.also.split(",") if n and n != args.workload])
     workers = min(16, os.cpu_count() or 1)
-    results, cpu = {}, None
+    results, fp8_results, cpu = {}, {}, None
     for name in names:
         w = CONFIGS[name]
         if args.heads:
@@ -312,6 +314,12 @@ def main():
             cpu = cpu_baseline(w, data, mask)
             log(f"  oracle: {cpu['value']:.5f} TOPS on {cpu['cores']} threads ({cpu['seconds']:.1f} s)")
         results[name] = (w, res)
+        if not args.no_fp8:
+            # the same workload with the FP8 (E4M3) P~V product: a variant, never the headline value
+            r8, _ = run_workload(w, data, args.steps, args.warmup, detail=False, pv_fp8=True)
+            log(f"  {name}, FP8 P~V: {r8['ms_per_step']:.3f} ms/step, {r8['tops']:.1f} dense-equivalent TOPS, "
+                f"attn kernel {r8['attn_kernel_ms']:.3f} ms, MFMA frac {r8['roofline']['frac']:.3f}")
+            fp8_results[name] = r8
         del data
 
     w, res = results[args.workload]
@@ -338,6 +346,11 @@ def main():
                                   "roofline": r2["roofline"],
                                   "detail": {k: v for k, v in r2.items()
                                              if k not in ("roofline", "tops", "ms_per_step", "sparsity")}}
+    if fp8_results:
+        line["fp8_pv_variant"] = {
+            name: {"dtype": "int8 QK^T + fp8 e4m3 P~V (fp32 softmax)", "value": r["tops"], "unit": "TOPS",
+                   "ms_per_step": r["ms_per_step"], "sparsity": r["sparsity"], "attn_kernel_ms": r["attn_kernel_ms"],
+                   "roofline": r["roofline"]} for name, r in fp8_results.items()}
     print(json.dumps(line))
 
 

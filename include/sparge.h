@@ -39,7 +39,9 @@ enum { SPARGE_F16 = 0, SPARGE_BF16 = 1 };
 enum { SPARGE_BQ = 128, SPARGE_BK = 64, SPARGE_ROW_GROUP = 32 };
 enum { SPARGE_MAX_HEADS = 128, SPARGE_MAX_TN = 4096 };
 /* see sparge_attn_quantized: how far (log2 units) a row's maximum may run ahead of the value subtracted inside exp */
-enum { SPARGE_REF_SLACK_LOG2 = 8 };
+enum { SPARGE_REF_SLACK_LOG2 = 8, SPARGE_REF_SLACK_LOG2_FP8 = 2 };
+/* sparge_desc.pv_dtype: type of the P~V product (Alg. 1 line 16) */
+enum { SPARGE_PV_16BIT = 0 /* the tensors' fp16/bf16 */, SPARGE_PV_FP8 = 1 /* OCP E4M3, see sparge_v_tiles */ };
 
 /* which entry point a workspace is sized for */
 enum { SPARGE_WS_QUANTIZE = 0, SPARGE_WS_PREDICT = 1, SPARGE_WS_ATTN = 2, SPARGE_WS_ATTN_QUANTIZED = 3,
@@ -49,6 +51,7 @@ typedef struct sparge_desc {
     int32_t B, H, N, d;
     int32_t dtype;                          /* SPARGE_F16 | SPARGE_BF16 */
     int64_t stride_b, stride_h, stride_n;   /* in elements; the d axis is contiguous */
+    int32_t pv_dtype;                       /* SPARGE_PV_16BIT | SPARGE_PV_FP8; only the attention entry points read it */
 } sparge_desc;
 
 /* Description of the last error on the calling thread (host string, never NULL). */
@@ -117,11 +120,23 @@ int sparge_attn_quantized(const int8_t* Qq, const int8_t* Kq, const float* q_sca
 
 /*
  * The two halves of sparge_attn_quantized, for callers that reuse V across calls or time the loop
- * alone.  sparge_v_tiles re-tiles V for the P~V product (Alg. 1 line 16): per (b,h) and key block j,
- * d rows of 64 key slots, keys >= N zero-filled; within every 16 keys the slot order is
- * {0-3, 8-11, 4-7, 12-15}.  v_tiles: 16-bit, [B,H,T_n,d,64], 16-byte aligned.
+ * alone.  sparge_v_tiles re-tiles V for the P~V product (Alg. 1 line 16); sparge_v_tiles_bytes gives
+ * the size of its output (16-byte aligned device memory).
+ * pv_dtype = SPARGE_PV_16BIT: per (b,h) and key block j, d rows of 64 key slots, keys >= N
+ *   zero-filled; within every 16 keys the slot order is {0-3, 8-11, 4-7, 12-15}; 16-bit [B,H,T_n,d,64].
+ * pv_dtype = SPARGE_PV_FP8 (the FP8 product the paper credits to its SageAttention2-based kernel,
+ *   Sec. 1 footnote; the paper gives no formulas, these are the library's):
+ *   delta_V[b,h,c] = fp32(max_t |V[b,h,t,c]|) / 448 in fp32 (0 for a zero channel),
+ *   V_hat = e4m3(fp32(V) / delta_V), OCP E4M3, round to nearest even; in the loop P~ is multiplied by
+ *   448 / 2^SPARGE_REF_SLACK_LOG2_FP8 (its largest possible value then is 448; the reference maximum
+ *   lags by at most SPARGE_REF_SLACK_LOG2_FP8 instead of SPARGE_REF_SLACK_LOG2) and rounded to E4M3;
+ *   products accumulate in fp32; O = (sum P~_q V_hat) delta_V / (scaled l); l sums the unrounded P~.
+ *   Output: E4M3 bytes [B,H,T_n,d/32,2,64,16]: (channel tile, key half h2, lane = c%32 + 32 g, byte b)
+ *   holds channel c of key 64 j + 32 h2 + 8 (b/4) + 4 g + b%4 (keys >= N are 0); then, 256-byte
+ *   aligned, delta_V fp32 [B,H,d]; then, 256-byte aligned, the fp32 bit patterns of the channel maxima.
  * sparge_attn_tiled is sparge_attn_quantized with V already in that form; it needs no workspace.
  */
+int sparge_v_tiles_bytes(const sparge_desc* desc, size_t* bytes /* host, out */);
 int sparge_v_tiles(const void* V, const sparge_desc* desc, void* v_tiles, void* hip_stream);
 int sparge_attn_tiled(const int8_t* Qq, const int8_t* Kq, const float* q_scale, const float* k_scale,
                       const void* v_tiles, const sparge_desc* desc, const uint8_t* mask,

@@ -19,5 +19,6 @@ from .binding import (  # noqa: F401
     sparge_workspace_bytes,
     tensor_from_numpy,
     REF_SLACK_LOG2,
+    REF_SLACK_LOG2_FP8,
     WS_ATTN, WS_ATTN_QUANTIZED, WS_FORWARD, WS_PREDICT, WS_QUANTIZE,
 )

@@ -15,7 +15,8 @@ import torch
 
 WS_QUANTIZE, WS_PREDICT, WS_ATTN, WS_ATTN_QUANTIZED, WS_FORWARD = range(5)
 BQ, BK = 128, 64
-REF_SLACK_LOG2 = 8  # SPARGE_REF_SLACK_LOG2 of sparge.h
+REF_SLACK_LOG2 = 8      # SPARGE_REF_SLACK_LOG2 of sparge.h
+REF_SLACK_LOG2_FP8 = 2  # SPARGE_REF_SLACK_LOG2_FP8
 
 _LIB: Optional[ctypes.CDLL] = None
 
@@ -27,7 +28,7 @@ class SpargeError(RuntimeError):
 class _Desc(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int32), ("d", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64),
-                ("stride_n", ctypes.c_int64)]
+                ("stride_n", ctypes.c_int64), ("pv_dtype", ctypes.c_int32)]
 
 
 def library_path() -> str:
@@ -57,6 +58,7 @@ def load_library() -> ctypes.CDLL:
     lib.sparge_attn_quantized.argtypes = [vp, vp, vp, vp, vp, dp, vp, f32p, ctypes.c_float, ctypes.c_int, vp, vp,
                                           vp, ctypes.c_size_t, vp]
     lib.sparge_v_tiles.argtypes = [vp, dp, vp, vp]
+    lib.sparge_v_tiles_bytes.argtypes = [dp, ctypes.POINTER(ctypes.c_size_t)]
     lib.sparge_attn_tiled.argtypes = [vp, vp, vp, vp, vp, dp, vp, f32p, ctypes.c_float, ctypes.c_int, vp, vp, vp]
     lib.sparge_set_timing_events.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.c_int]
     lib.sparge_set_timing_events.restype = ctypes.c_int
@@ -65,7 +67,7 @@ def load_library() -> ctypes.CDLL:
     lib.sparge_forward.argtypes = [vp, vp, vp, dp, f32p, f32p, f32p, ctypes.c_float, ctypes.c_int, vp, vp, vp, vp,
                                    ctypes.c_size_t, vp]
     for name in ("sparge_workspace_bytes", "sparge_quantize", "sparge_predict", "sparge_attn_quantized",
-                 "sparge_attn", "sparge_forward", "sparge_v_tiles", "sparge_attn_tiled"):
+                 "sparge_attn", "sparge_forward", "sparge_v_tiles", "sparge_attn_tiled", "sparge_v_tiles_bytes"):
         getattr(lib, name).restype = ctypes.c_int
     _LIB = lib
     return lib
@@ -76,7 +78,7 @@ def _check(rc: int) -> None:
         raise SpargeError(f"libsparge error {rc}: {load_library().sparge_last_error().decode()}")
 
 
-def _desc(x: torch.Tensor) -> _Desc:
+def _desc(x: torch.Tensor, pv_fp8: bool = False) -> _Desc:
     if x.dim() != 4:
         raise SpargeError("expected a [B, H, N, d] tensor")
     if not x.is_cuda:
@@ -90,7 +92,7 @@ def _desc(x: torch.Tensor) -> _Desc:
     else:
         raise SpargeError(f"dtype {x.dtype} not supported (fp16 or bf16)")
     B, H, N, d = x.shape
-    return _Desc(B, H, N, d, dt, x.stride(0), x.stride(1), x.stride(2))
+    return _Desc(B, H, N, d, dt, x.stride(0), x.stride(1), x.stride(2), 1 if pv_fp8 else 0)
 
 
 def _same_layout(ref: torch.Tensor, *others: torch.Tensor) -> None:
@@ -125,15 +127,15 @@ def sparge_version() -> int:
     return load_library().sparge_version()
 
 
-def sparge_workspace_bytes(x: torch.Tensor, entry: int) -> int:
+def sparge_workspace_bytes(x: torch.Tensor, entry: int, pv_fp8: bool = False) -> int:
     n = ctypes.c_size_t(0)
-    d = _desc(x)
+    d = _desc(x, pv_fp8)
     _check(load_library().sparge_workspace_bytes(ctypes.byref(d), entry, ctypes.byref(n)))
     return int(n.value)
 
 
-def _workspace(x: torch.Tensor, entry: int, ws: Optional[torch.Tensor]) -> torch.Tensor:
-    need = sparge_workspace_bytes(x, entry)
+def _workspace(x: torch.Tensor, entry: int, ws: Optional[torch.Tensor], pv_fp8: bool = False) -> torch.Tensor:
+    need = sparge_workspace_bytes(x, entry, pv_fp8)
     if ws is None:
         ws = torch.empty(need, dtype=torch.uint8, device=x.device)
     return ws
@@ -180,9 +182,11 @@ def sparge_predict(Q: torch.Tensor, K: torch.Tensor, tau, theta, causal: bool = 
 
 def sparge_attn_quantized(Qq, Kq, q_scale, k_scale, V: torch.Tensor, mask: Optional[torch.Tensor], lam,
                           causal: bool = False, sm_scale: float = 0.0, return_stats: bool = False,
-                          ws: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None):
-    """-> O (same layout as V) (and stats uint64-as-int64 [B,H,4] if return_stats)."""
-    d = _desc(V)
+                          ws: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                          pv_fp8: bool = False):
+    """-> O (same layout as V) (and stats uint64-as-int64 [B,H,4] if return_stats).
+    pv_fp8: the P~V product in FP8 (E4M3) instead of V's 16-bit type."""
+    d = _desc(V, pv_fp8)
     B, H, N, dim = V.shape
     Tm, Tn = _blocks(N)
     for t, shape, dt in ((Qq, (B, H, N, dim), torch.int8), (Kq, (B, H, N, dim), torch.int8),
@@ -195,30 +199,43 @@ def sparge_attn_quantized(Qq, Kq, q_scale, k_scale, V: torch.Tensor, mask: Optio
     O = torch.empty_like(V) if out is None else out
     _same_layout(V, O)
     stats = torch.zeros((B, H, 4), dtype=torch.int64, device=V.device) if return_stats else None
-    ws = _workspace(V, WS_ATTN_QUANTIZED, ws)
+    ws = _workspace(V, WS_ATTN_QUANTIZED, ws, pv_fp8)
     _check(load_library().sparge_attn_quantized(_ptr(Qq), _ptr(Kq), _ptr(q_scale), _ptr(k_scale), _ptr(V),
                                                 ctypes.byref(d), _ptr(mask), _per_head(lam, H), float(sm_scale),
                                                 int(causal), _ptr(O), _ptr(stats), _ptr(ws), ws.numel(), _stream()))
     return (O, stats) if return_stats else O
 
 
-def sparge_v_tiles(V: torch.Tensor) -> torch.Tensor:
-    """-> V re-tiled for the P~V product: [B,H,Tn,d,64], V's dtype."""
-    d = _desc(V)
+def sparge_v_tiles(V: torch.Tensor, pv_fp8: bool = False) -> torch.Tensor:
+    """-> V re-tiled for the P~V product: [B,H,Tn,d,64] in V's dtype, or (pv_fp8) a flat uint8 buffer holding
+    the E4M3 tiles, the channel scales and the channel maxima (layout: sparge.h)."""
+    d = _desc(V, pv_fp8)
     B, H, N, dim = V.shape
-    tiles = torch.empty((B, H, _blocks(N)[1], dim, BK), dtype=V.dtype, device=V.device)
+    if pv_fp8:
+        n = ctypes.c_size_t(0)
+        _check(load_library().sparge_v_tiles_bytes(ctypes.byref(d), ctypes.byref(n)))
+        tiles = torch.empty(n.value, dtype=torch.uint8, device=V.device)
+    else:
+        tiles = torch.empty((B, H, _blocks(N)[1], dim, BK), dtype=V.dtype, device=V.device)
     _check(load_library().sparge_v_tiles(_ptr(V), ctypes.byref(d), _ptr(tiles), _stream()))
     return tiles
 
 
 def sparge_attn_tiled(Qq, Kq, q_scale, k_scale, v_tiles: torch.Tensor, like: torch.Tensor,
                       mask: Optional[torch.Tensor], lam, causal: bool = False, sm_scale: float = 0.0,
-                      stats: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None):
+                      stats: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                      pv_fp8: bool = False):
     """The sparse flash loop alone.  `like` gives O's shape/strides/dtype (the V it was tiled from)."""
-    d = _desc(like)
+    d = _desc(like, pv_fp8)
     B, H, N, dim = like.shape
-    if tuple(v_tiles.shape) != (B, H, _blocks(N)[1], dim, BK) or not v_tiles.is_contiguous():
-        raise SpargeError("v_tiles must come from sparge_v_tiles for this shape")
+    if pv_fp8:
+        n = ctypes.c_size_t(0)
+        _check(load_library().sparge_v_tiles_bytes(ctypes.byref(d), ctypes.byref(n)))
+        ok = v_tiles.dtype == torch.uint8 and v_tiles.numel() == n.value
+    else:
+        ok = tuple(v_tiles.shape) == (B, H, _blocks(N)[1], dim, BK)
+    if not ok or not v_tiles.is_contiguous():
+        raise SpargeError("v_tiles must come from sparge_v_tiles for this shape and pv_fp8 setting")
     O = torch.empty_like(like) if out is None else out
     _same_layout(like, O)
     _check(load_library().sparge_attn_tiled(_ptr(Qq), _ptr(Kq), _ptr(q_scale), _ptr(k_scale), _ptr(v_tiles),
@@ -228,10 +245,11 @@ def sparge_attn_tiled(Qq, Kq, q_scale, k_scale, v_tiles: torch.Tensor, like: tor
 
 
 def sparge_attn(Q, K, V, mask: Optional[torch.Tensor], lam, causal: bool = False, sm_scale: float = 0.0,
-                return_stats: bool = False, ws: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None):
+                return_stats: bool = False, ws: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                pv_fp8: bool = False):
     """Quantize + sparse attention.  -> O (and stats)."""
     _same_layout(Q, K, V)
-    d = _desc(Q)
+    d = _desc(Q, pv_fp8)
     B, H, N, _ = Q.shape
     Tm, Tn = _blocks(N)
     if mask is not None and (tuple(mask.shape) != (B, H, Tm, Tn) or mask.dtype != torch.uint8
@@ -240,7 +258,7 @@ def sparge_attn(Q, K, V, mask: Optional[torch.Tensor], lam, causal: bool = False
     O = torch.empty_like(V) if out is None else out
     _same_layout(V, O)
     stats = torch.zeros((B, H, 4), dtype=torch.int64, device=Q.device) if return_stats else None
-    ws = _workspace(Q, WS_ATTN, ws)
+    ws = _workspace(Q, WS_ATTN, ws, pv_fp8)
     _check(load_library().sparge_attn(_ptr(Q), _ptr(K), _ptr(V), ctypes.byref(d), _ptr(mask), _per_head(lam, H),
                                       float(sm_scale), int(causal), _ptr(O), _ptr(stats), _ptr(ws), ws.numel(),
                                       _stream()))
@@ -249,17 +267,17 @@ def sparge_attn(Q, K, V, mask: Optional[torch.Tensor], lam, causal: bool = False
 
 def sparge_forward(Q, K, V, tau, theta, lam, causal: bool = False, sm_scale: float = 0.0,
                    return_mask: bool = False, return_stats: bool = False, ws: Optional[torch.Tensor] = None,
-                   out: Optional[torch.Tensor] = None):
+                   out: Optional[torch.Tensor] = None, pv_fp8: bool = False):
     """All of Algorithm 1.  -> O (and mask, stats when requested, in that order)."""
     _same_layout(Q, K, V)
-    d = _desc(Q)
+    d = _desc(Q, pv_fp8)
     B, H, N, _ = Q.shape
     Tm, Tn = _blocks(N)
     O = torch.empty_like(V) if out is None else out
     _same_layout(V, O)
     mask = torch.empty((B, H, Tm, Tn), dtype=torch.uint8, device=Q.device) if return_mask else None
     stats = torch.zeros((B, H, 4), dtype=torch.int64, device=Q.device) if return_stats else None
-    ws = _workspace(Q, WS_FORWARD, ws)
+    ws = _workspace(Q, WS_FORWARD, ws, pv_fp8)
     _check(load_library().sparge_forward(_ptr(Q), _ptr(K), _ptr(V), ctypes.byref(d), _per_head(tau, H),
                                          _per_head(theta, H), _per_head(lam, H), float(sm_scale), int(causal),
                                          _ptr(O), _ptr(mask), _ptr(stats), _ptr(ws), ws.numel(), _stream()))

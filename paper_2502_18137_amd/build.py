@@ -22,6 +22,7 @@ SOURCES = {
     "stats_quant.hip": ["-ffp-contract=off"],
     "predict.hip": ["-ffp-contract=off"],
     "attn.hip": [],
+    "v_fp8.hip": ["-ffp-contract=off"],
     "api.hip": [],
 }
 

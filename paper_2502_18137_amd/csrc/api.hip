@@ -45,7 +45,38 @@ int check_desc(const sparge_desc* d, Shape* s) {
     s->sb = d->stride_b; s->sh = d->stride_h; s->sn = d->stride_n;
     s->Tm = (d->N + BQ - 1) / BQ;
     s->Tn = Tn;
+    if (d->pv_dtype != SPARGE_PV_16BIT && d->pv_dtype != SPARGE_PV_FP8)
+        return fail(SPARGE_EUNSUPPORTED, "pv_dtype %d not supported", d->pv_dtype);
+    s->pv_fp8 = d->pv_dtype == SPARGE_PV_FP8;
     return SPARGE_OK;
+}
+
+// Re-tiled V: the tiles, and for the FP8 product the channel scales and maxima behind them.
+struct VTiles {
+    size_t scale, amax, total;
+};
+VTiles v_tiles_layout(const Shape& s) {
+    const size_t BH = (size_t)s.B * s.H;
+    VTiles v{};
+    if (!s.pv_fp8) {
+        v.total = BH * s.Tn * s.d * BK * sizeof(uint16_t);
+        return v;
+    }
+    v.scale = align256(BH * s.Tn * s.d * BK);
+    v.amax = v.scale + align256(BH * s.d * sizeof(float));
+    v.total = v.amax + align256(BH * s.d * sizeof(uint32_t));
+    return v;
+}
+hipError_t retile_v(const void* V, const Shape& s, void* v_tiles, hipStream_t st) {
+    if (!s.pv_fp8) return launch_v_tiles(V, s, static_cast<uint16_t*>(v_tiles), st);
+    const VTiles v = v_tiles_layout(s);
+    char* p = static_cast<char*>(v_tiles);
+    return launch_v_tiles_fp8(V, s, reinterpret_cast<unsigned char*>(p), reinterpret_cast<float*>(p + v.scale),
+                              reinterpret_cast<uint32_t*>(p + v.amax), st);
+}
+const float* v_scale_of(const void* v_tiles, const Shape& s) {
+    return s.pv_fp8 ? reinterpret_cast<const float*>(static_cast<const char*>(v_tiles) + v_tiles_layout(s).scale)
+                    : nullptr;
 }
 
 bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
@@ -75,7 +106,7 @@ Workspace plan(const Shape& s, int entry) {
     w.Kq = take(quant_in_ws, BH * s.N * s.d);
     w.q_scale = take(quant_in_ws, BH * s.Tm * sizeof(float));
     w.k_scale = take(quant_in_ws, BH * s.Tn * sizeof(float));
-    w.v_tiles = take(attn, BH * s.Tn * s.d * BK * sizeof(uint16_t));
+    w.v_tiles = take(attn, v_tiles_layout(s).total);
     w.mask = take(entry == SPARGE_WS_FORWARD, BH * s.Tm * s.Tn);
     w.total = off ? off : 256;
     return w;
@@ -143,7 +174,7 @@ int run_predict(const Shape& s, void* ws, const Workspace& w, const HeadParams& 
 
 // The attention launch, bracketed by the caller's timing events when some are installed.
 int timed_attn(const int8_t* Qq, const int8_t* Kq, const float* q_scale, const float* k_scale,
-               const uint16_t* v_tiles, const Shape& s, const uint8_t* mask, const HeadParams& lam, float sm_scale,
+               const void* v_tiles, const Shape& s, const uint8_t* mask, const HeadParams& lam, float sm_scale,
                int causal, void* O, uint64_t* stats, hipStream_t st) {
     const bool timed = g_ev_start && g_ev_k < g_ev_n;
     hipError_t e;
@@ -151,7 +182,7 @@ int timed_attn(const int8_t* Qq, const int8_t* Kq, const float* q_scale, const f
         return hip_fail(e, "zero stats");
     if (timed && (e = hipEventRecord(static_cast<hipEvent_t>(g_ev_start[g_ev_k]), st)) != hipSuccess)
         return hip_fail(e, "record start event");
-    if ((e = launch_attn(Qq, Kq, q_scale, k_scale, v_tiles, s, mask, lam, sm_scale, causal, O,
+    if ((e = launch_attn(Qq, Kq, q_scale, k_scale, v_tiles, v_scale_of(v_tiles, s), s, mask, lam, sm_scale, causal, O,
                          reinterpret_cast<unsigned long long*>(stats), st)) != hipSuccess)
         return hip_fail(e, "attn");
     if (timed) {
@@ -163,10 +194,10 @@ int timed_attn(const int8_t* Qq, const int8_t* Kq, const float* q_scale, const f
 }
 
 int run_attn(const int8_t* Qq, const int8_t* Kq, const float* q_scale, const float* k_scale, const void* V,
-             const Shape& s, uint16_t* v_tiles, const uint8_t* mask, const HeadParams& lam, float sm_scale,
+             const Shape& s, void* v_tiles, const uint8_t* mask, const HeadParams& lam, float sm_scale,
              int causal, void* O, uint64_t* stats, hipStream_t st) {
     hipError_t e;
-    if ((e = launch_v_tiles(V, s, v_tiles, st)) != hipSuccess) return hip_fail(e, "v_tiles");
+    if ((e = retile_v(V, s, v_tiles, st)) != hipSuccess) return hip_fail(e, "v_tiles");
     return timed_attn(Qq, Kq, q_scale, k_scale, v_tiles, s, mask, lam, sm_scale, causal, O, stats, st);
 }
 
@@ -243,8 +274,17 @@ int sparge_attn_quantized(const int8_t* Qq, const int8_t* Kq, const float* q_sca
     if ((rc = check_lambda(lambda, s.H, &lam))) return rc;
     const Workspace w = plan(s, SPARGE_WS_ATTN_QUANTIZED);
     if ((rc = check_ws(w, ws, ws_bytes))) return rc;
-    return run_attn(Qq, Kq, q_scale, k_scale, V, s, at<uint16_t>(ws, w.v_tiles), mask, lam, sm_scale, causal, O,
+    return run_attn(Qq, Kq, q_scale, k_scale, V, s, at<char>(ws, w.v_tiles), mask, lam, sm_scale, causal, O,
                     stats, static_cast<hipStream_t>(hip_stream));
+}
+
+int sparge_v_tiles_bytes(const sparge_desc* desc, size_t* bytes) {
+    Shape s;
+    int rc = check_desc(desc, &s);
+    if (rc) return rc;
+    if (!bytes) return fail(SPARGE_EINVAL, "bytes is NULL");
+    *bytes = v_tiles_layout(s).total;
+    return SPARGE_OK;
 }
 
 int sparge_v_tiles(const void* V, const sparge_desc* desc, void* v_tiles, void* hip_stream) {
@@ -253,7 +293,7 @@ int sparge_v_tiles(const void* V, const sparge_desc* desc, void* v_tiles, void* 
     if (rc) return rc;
     if (!V || !v_tiles) return fail(SPARGE_EINVAL, "NULL tensor argument");
     if (misaligned(V) || misaligned(v_tiles)) return fail(SPARGE_EINVAL, "tensor pointers must be 16-byte aligned");
-    hipError_t e = launch_v_tiles(V, s, static_cast<uint16_t*>(v_tiles), static_cast<hipStream_t>(hip_stream));
+    hipError_t e = retile_v(V, s, v_tiles, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? SPARGE_OK : hip_fail(e, "v_tiles");
 }
 
@@ -268,7 +308,7 @@ int sparge_attn_tiled(const int8_t* Qq, const int8_t* Kq, const float* q_scale, 
         return fail(SPARGE_EINVAL, "tensor pointers must be 16-byte aligned");
     HeadParams lam;
     if ((rc = check_lambda(lambda, s.H, &lam))) return rc;
-    return timed_attn(Qq, Kq, q_scale, k_scale, static_cast<const uint16_t*>(v_tiles), s, mask, lam, sm_scale, causal,
+    return timed_attn(Qq, Kq, q_scale, k_scale, v_tiles, s, mask, lam, sm_scale, causal,
                       O, stats, static_cast<hipStream_t>(hip_stream));
 }
 
@@ -291,7 +331,7 @@ int sparge_attn(const void* Q, const void* K, const void* V, const sparge_desc* 
                                   at<float>(ws, w.q_scale), at<int8_t>(ws, w.Kq), at<float>(ws, w.k_scale),
                                   at<float>(ws, w.k_mean), st))) return rc;
     return run_attn(at<int8_t>(ws, w.Qq), at<int8_t>(ws, w.Kq), at<float>(ws, w.q_scale), at<float>(ws, w.k_scale),
-                    V, s, at<uint16_t>(ws, w.v_tiles), mask, lam, sm_scale, causal, O, stats, st);
+                    V, s, at<char>(ws, w.v_tiles), mask, lam, sm_scale, causal, O, stats, st);
 }
 
 int sparge_forward(const void* Q, const void* K, const void* V, const sparge_desc* desc, const float* tau,
@@ -316,7 +356,7 @@ int sparge_forward(const void* Q, const void* K, const void* V, const sparge_des
     uint8_t* mask = mask_out ? mask_out : at<uint8_t>(ws, w.mask);
     if ((rc = run_predict(s, ws, w, t, th, sm_scale, causal, mask, st))) return rc;
     return run_attn(at<int8_t>(ws, w.Qq), at<int8_t>(ws, w.Kq), at<float>(ws, w.q_scale), at<float>(ws, w.k_scale),
-                    V, s, at<uint16_t>(ws, w.v_tiles), mask, lam, sm_scale, causal, O, stats, st);
+                    V, s, at<char>(ws, w.v_tiles), mask, lam, sm_scale, causal, O, stats, st);
 }
 
 int sparge_set_timing_events(void* const* starts, void* const* stops, int n) {

@@ -16,6 +16,7 @@ struct Shape {
     int B, H, N, d, dtype;
     long long sb, sh, sn;  // element strides of the 16-bit tensors
     int Tm, Tn;
+    int pv_fp8;            // P~V product in FP8 (E4M3) instead of the tensors' 16-bit type
 };
 
 // Per-head scalars travel to the device inside the kernel argument block.
@@ -80,7 +81,12 @@ hipError_t launch_v_tiles(const void* V, const Shape& s, uint16_t* v_tiles, hipS
 hipError_t launch_zero_stats(unsigned long long* stats, int n, hipStream_t st);
 // The sparse flash loop (accumulates into stats).
 hipError_t launch_attn(const int8_t* Qq, const int8_t* Kq, const float* q_scale, const float* k_scale,
-                       const uint16_t* v_tiles, const Shape& s, const uint8_t* mask, const HeadParams& lambda,
-                       float sm_scale, int causal, void* O, unsigned long long* stats, hipStream_t st);
+                       const void* v_tiles, const float* v_scale, const Shape& s, const uint8_t* mask,
+                       const HeadParams& lambda, float sm_scale, int causal, void* O, unsigned long long* stats,
+                       hipStream_t st);
+// FP8 form of V: per-(b,h,channel) |V| maxima (as fp32 bit patterns, zeroed here), scales amax/448, and
+// E4M3 tiles in the operand order of the 32x32x64 MFMA.
+hipError_t launch_v_tiles_fp8(const void* V, const Shape& s, unsigned char* tiles, float* v_scale,
+                              uint32_t* amax_bits, hipStream_t st);
 
 }  // namespace sparge

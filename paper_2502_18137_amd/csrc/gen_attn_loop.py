@@ -37,10 +37,11 @@ u+1 that does not exist counts as fully masked, which makes the last iteration (
 score) and the drain (u = cnt: only P~V of the last tile) ordinary masked iterations.  Iteration 0
 enters with execp = 0: nothing is pending.
 """
+import math
 import os
 
 MAGIC_NEG = 0xCB400000  # bit pattern of -12582912.0f = -(1.5 * 2^23)
-RESCALE_T = 0x41000000  # 8.0f
+RESCALE_T = {8: 0x41000000, 2: 0x40000000}  # 8.0f, 2.0f
 LA = 4                  # operand reads run this many slots ahead; they are issued and awaited in pairs
 RING = LA + 2
 PRE_UNITS = 10          # vector work placed before the first MFMA of a step (covers the LDS latency)
@@ -51,9 +52,16 @@ class Cfg:
     def __init__(self, D, dt):
         self.D, self.dt = D, dt
         self.NSTEP = self.NDT = D // 32
-        self.NQK, self.NPV = 2 * self.NSTEP, 4 * self.NDT
+        self.fp8 = dt == "fp8"
+        # P~V: 16-bit 32x32x16 MFMAs (4 key steps per channel tile) or one FP8 32x32x64 MFMA per channel tile
+        self.NQK, self.NPV = 2 * self.NSTEP, (self.NDT if self.fp8 else 4 * self.NDT)
         self.NSLOT = self.NQK + self.NPV
-        self.K_BYTES, self.V_BYTES = 64 * D, D * 128
+        self.NUNIT = self.NQK + (2 * self.NDT if self.fp8 else self.NPV)   # 16-byte operand reads per step
+        self.K_BYTES, self.V_BYTES = 64 * D, (D * 64 if self.fp8 else D * 128)
+        self.NP = 2 if self.fp8 else 4           # registers quads of one P~ tile
+        # how far the row maximum may run ahead of the reference (log2 units); with FP8 P~ is scaled by
+        # 448 / 2^T so that its largest possible value is the largest E4M3 number
+        self.T_LOG2 = 2 if self.fp8 else 8
         self.KD, self.VD = self.K_BYTES // (1024 * NWAVE), self.V_BYTES // (1024 * NWAVE)  # copies per wave
         self.NDMA = self.KD + self.VD
         # ---- VGPRs (pinned; the kernel uses no AGPRs, so all 256 registers of a wave are VGPRs) ----
@@ -108,23 +116,37 @@ def gen_step(c, o, cur, NST, kbuf, vbuf, masked, pv, dkbuf, dvbuf, label, late):
     T0, T1, T2 = c.T, c.T + 1, c.T + 2
 
     NSLOT = c.NSLOT if pv else c.NQK  # without the P~V product only the score MFMAs remain
+    NUNIT = c.NUNIT if pv else c.NQK  # operand reads (16 bytes per lane each)
+    # MFMA slot -> (first operand unit, units): an FP8 P~V MFMA takes two
+    if c.fp8:
+        slot_units = [(sl, 1) for sl in range(c.NQK)] + [(c.NQK + 2 * dt, 2) for dt in range(c.NDT)]
+    else:
+        slot_units = [(sl, 1) for sl in range(c.NSLOT)]
 
-    def read(sl):
-        dst = c.RG + 4 * (sl % RING)
-        if sl < c.NQK:
-            kh, st = sl % 2, sl // 2
+    def read(un):
+        dst = c.RG + 4 * (un % RING)
+        if un < c.NQK:
+            kh, st = un % 2, un // 2
             o(f"ds_read_b128 {vr(dst, 4)}, v{c.KA + st} offset:{kbuf * c.K_BYTES + kh * 32 * c.D}")
+        elif c.fp8:
+            dt, h2 = divmod(un - c.NQK, 2)
+            o(f"ds_read_b128 {vr(dst, 4)}, v{c.VA} offset:{vbuf * c.V_BYTES + dt * 2048 + h2 * 1024}")
         else:
-            ks, dt = divmod(sl - c.NQK, c.NDT)
+            ks, dt = divmod(un - c.NQK, c.NDT)
             o(f"ds_read_b128 {vr(dst, 4)}, v{c.VA + ks} offset:{vbuf * c.V_BYTES + dt * 4096}")
 
     def mfma(sl):
-        src = c.RG + 4 * (sl % RING)
+        un, _ = slot_units[sl]
+        src = c.RG + 4 * (un % RING)
         if sl < c.NQK:
             kh, st = sl % 2, sl // 2
             d = YS + 16 * kh
             acc = vr(c.MG, 16) if st == 0 else vr(d, 16)
             o(f"v_mfma_i32_32x32x32_i8 {vr(d, 16)}, {vr(src, 4)}, {vr(c.Q + 4 * st, 4)}, {acc}")
+        elif c.fp8:
+            dt = sl - c.NQK
+            a = c.O + 16 * dt
+            o(f"v_mfma_f32_32x32x64_f8f6f4 {vr(a, 16)}, {vr(src, 8)}, {vr(YP, 8)}, {vr(a, 16)}")
         else:
             ks, dt = divmod(sl - c.NQK, c.NDT)
             a = c.O + 16 * dt
@@ -136,7 +158,11 @@ def gen_step(c, o, cur, NST, kbuf, vbuf, masked, pv, dkbuf, dvbuf, label, late):
     F = lambda e: ops.append((f"v_fma_f32 v{x(e)}, v{x(e)}, s{s['scx']}, v{c.CX}", 1))
     E = lambda e: ops.append((f"v_exp_f32 v{x(e)}, v{x(e)}", 2))
     A = lambda e: ops.append((f"v_add_f32 v{c.L}, v{c.L}, v{x(e)}", 1))
-    C = lambda w: ops.append((f"v_cvt_pk_{c.dt}_f32 v{XP + w}, v{x(2 * w)}, v{x(2 * w + 1)}", 1))
+    if c.fp8:   # two E4M3 values into the low or the high half of a register
+        C = lambda w: ops.append((f"v_cvt_pk_fp8_f32 v{XP + w // 2}, v{x(2 * w)}, v{x(2 * w + 1)}"
+                                  + (" op_sel:[0,0,1]" if w % 2 else ""), 1))
+    else:
+        C = lambda w: ops.append((f"v_cvt_pk_{c.dt}_f32 v{XP + w}, v{x(2 * w)}, v{x(2 * w + 1)}", 1))
     for k in range(16):
         F(2 * k); F(2 * k + 1); E(2 * k); E(2 * k + 1)
         if k:
@@ -179,19 +205,31 @@ def gen_step(c, o, cur, NST, kbuf, vbuf, masked, pv, dkbuf, dvbuf, label, late):
 
     # chunk 0 runs before the first MFMA, chunk sl + 1 after MFMA sl
     if pv:
-        total = sum(u for _, u in ops)
-        per_slot = (total - PRE_UNITS) / NSLOT
-        chunks, acc_u, idx = [], 0.0, 0
-        for k in range(NSLOT + 1):
-            target = PRE_UNITS + per_slot * k
-            ch = []
-            while idx < len(ops) and (acc_u + ops[idx][1] / 2 <= target or k == NSLOT):
-                if idx == first_max:
-                    # the fresh scores are complete a few slots after the last Q K^T MFMA
-                    assert k - 1 >= c.NQK + 1, "row-maximum work scheduled too early"
-                ch.append(ops[idx][0]); acc_u += ops[idx][1]
-                idx += 1
-            chunks.append(ch)
+        def spread(part, weights, pre):
+            """part's instructions over len(weights) + 1 consecutive chunks: `pre` issue units in the first
+            one, the rest behind the MFMAs in proportion to the time each MFMA occupies the matrix pipe."""
+            total = sum(u for _, u in part)
+            wsum = max(sum(weights), 1)
+            out, acc_u, idx, wacc = [], 0.0, 0, 0
+            for k in range(len(weights) + 1):
+                target = pre + (total - pre) * wacc / wsum
+                ch = []
+                while idx < len(part) and (acc_u + part[idx][1] / 2 <= target or k == len(weights)):
+                    ch.append(part[idx][0]); acc_u += part[idx][1]
+                    idx += 1
+                out.append(ch)
+                if k < len(weights):
+                    wacc += weights[k]
+            return out
+        # an FP8 32x32x64 MFMA runs twice as long as the others
+        wts = [2 if (c.fp8 and sl >= c.NQK) else 1 for sl in range(NSLOT)]
+        # the fresh scores are complete a few slots after the last Q K^T MFMA: nothing that reads them
+        # comes before chunk kmin
+        kmin = c.NQK + (1 if c.fp8 else 2)
+        chunks = spread(ops, wts, PRE_UNITS)
+        if sum(len(ch) for ch in chunks[:kmin]) > first_max:
+            chunks = spread(ops[:first_max], wts[:kmin - 1], PRE_UNITS) + spread(ops[first_max:], wts[kmin:], 0)
+        assert sum(len(ch) for ch in chunks[:kmin]) <= first_max and len(chunks) == NSLOT + 1
     else:
         # the score MFMAs are the only ones: the softmax stream is spread over their slots, at least 20
         # of its instructions stay behind the last MFMA, and the work on the fresh scores follows them
@@ -220,12 +258,16 @@ def gen_step(c, o, cur, NST, kbuf, vbuf, masked, pv, dkbuf, dvbuf, label, late):
     o(f"ds_read_b32 v{c.L2}, v{c.PS} offset:8")                 # scale of tile u+2
     if masked:
         o(f"ds_read_u16 v{c.L3}, v{c.PJ} offset:2")             # key block of tile u+1
-    for sl in range(LA):
-        read(sl)
+    for un in range(LA):
+        read(un)
     o(f"v_add_u32 v{c.PJ}, 2, v{c.PJ}")
     o(f"v_add_u32 v{c.PS}, 4, v{c.PS}")
     o(f"v_mov_b32 v{c.CX}, s{s['negmagic']}")
     o(f"v_fma_f32 v{c.CX}, v{c.CX}, s{s['scx']}, -v{c.MR}")   # -(bias * scale) - reference maximum
+    if c.fp8:  # P~ is scaled by 448 / 2^T onto the E4M3 range
+        import struct
+        bits = struct.unpack("<I", struct.pack("<f", math.log2(448.0) - c.T_LOG2))[0]
+        o(f"v_add_f32 v{c.CX}, 0x{bits:08x}, v{c.CX}")
     if masked:  # a row that has not seen a key yet (reference -inf) only has masked scores here
         o(f"v_cmp_eq_f32 vcc, 0xff800000, v{c.MR}")
         o(f"v_cndmask_b32_e64 v{c.CX}, v{c.CX}, 0, vcc")
@@ -235,11 +277,12 @@ def gen_step(c, o, cur, NST, kbuf, vbuf, masked, pv, dkbuf, dvbuf, label, late):
         o(t)
     tag = f"{label}"
     for sl in range(NSLOT):
-        if sl % 2 == 0:
-            issued = min(NSLOT, sl + LA + 2)
-            for t in range(sl + LA, issued):
+        un, nu = slot_units[sl]
+        if un % 2 == 0:   # a new pair of operand units begins: request the pair LA units ahead, wait for this one
+            issued = min(NUNIT, un + LA + 2)
+            for t in range(un + LA, issued):
                 read(t)
-            o(f"s_waitcnt lgkmcnt({issued - (sl + 2)})")      # the operands of this slot and the next have arrived
+            o(f"s_waitcnt lgkmcnt({issued - (un + 2)})")
         mfma(sl)
         ch = list(chunks[sl + 1])
         if sl == 0:
@@ -333,7 +376,7 @@ def gen_loop(c, NST):
     o = lines.append
     period = 2 * NST if NST % 2 else NST  # bodies: one set per value of u mod lcm(2, NST)
     o(f"s_mov_b32 s{s['negmagic']}, 0x{MAGIC_NEG:08x}")
-    o(f"s_mov_b32 s{s['rt']}, 0x{RESCALE_T:08x}")
+    o(f"s_mov_b32 s{s['rt']}, 0x{RESCALE_T[c.T_LOG2]:08x}")
     o(f"s_cmp_lg_u32 s{s['exec']}, 0")                 # stage-2 decision of tile 0 as a lane mask
     o(f"s_cselect_b64 {sp(s, 'ex0')}, -1, 0")
     o(f"s_mov_b64 {sp(s, 'exp0')}, 0")                 # nothing is pending: iteration 0 has no P~V
@@ -401,7 +444,7 @@ def clobbers(c):
 def gen_function(c, NST):
     s = c.sg
     body = gen_loop(c, NST)
-    dtn = "SPARGE_BF16" if c.dt == "bf16" else "SPARGE_F16"
+    dtn = {"bf16": "SPARGE_BF16", "f16": "SPARGE_F16", "fp8": "PV_FP8"}[c.dt]
     io_names = "u jk jv scn scx pv".split()                       # read and written by the block
     in_names = "exec jpart cnt ufull ldskd ldsvd ldsjl ldsscl lam2".split()
     floats = {"scn", "scx", "lam2"}
@@ -426,7 +469,7 @@ def gen_function(c, NST):
     for b in range(2):
         for kh in range(2):
             outs.append(f'"+{{{vr(c.S[b] + 16 * kh, 16)}}}"(w.S[{b}][{kh}])')
-        for ks in range(4):
+        for ks in range(c.NP):
             outs.append(f'"+{{{vr(c.P[b] + 4 * ks, 4)}}}"(w.P[{b}][{ks}])')
     for reg, expr in ((c.MT, "w.m_true"), (c.MR, "w.m_ref"), (c.L, "w.l")):
         outs.append(f'"+{{v{reg}}}"({expr})')
@@ -467,7 +510,7 @@ def main():
     out = ["// GENERATED by gen_attn_loop.py -- do not edit; edit the generator and run it again.",
            "// Steady-state iterations of the sparse flash loop as hand-scheduled gfx950 assembly.", ""]
     for D in (64, 128):
-        for dt in ("f16", "bf16"):
+        for dt in ("f16", "bf16", "fp8"):
             for NST in (2, 3):
                 out += gen_function(Cfg(D, dt), NST)
     with open(os.path.join(here, "attn_loop_gfx950.inc"), "w") as f:
