@@ -99,9 +99,27 @@ def test_full_configuration(sp, name):
               flush=True)
         assert err <= 2e-3
 
+    # ---- the FP8 (E4M3) P~V product on the same inputs: same mask and tile counters; sampled rows of one head
+    O8, mask8, stats8 = sp.sparge_forward(Q, K, V, w.tau, w.theta, w.lam, causal=w.causal, return_mask=True,
+                                          return_stats=True, pv_fp8=True)
+    torch.cuda.synchronize()
+    assert torch.equal(mask8, mask) and torch.isfinite(O8.float()).all()
+    s8 = stats8.cpu().numpy()
+    assert (s8[0, :, [0, 2, 3]] == stats_np[0, :, [0, 2, 3]]).all()
+    h = w.H - 1
+    ref8 = so.sparse_attention(x["q"][0, h], x["k"][0, h], x["v"][0, h], mask_np[0, h], lam=f32(w.lam),
+                               causal=w.causal, quant=True, pv_dtype="fp8e4m3", q_blocks=blocks,
+                               ref_slack=sp.REF_SLACK_LOG2_FP8 * math.log(2.0))
+    got8 = O8[0, h].float().cpu().numpy().astype(np.float64)[rows]
+    err8 = so.rel_l1(got8, so.round16(ref8.O[rows], w.dtype))
+    print(f"  head {h}, FP8 P~V: rel-L1 vs oracle {err8:.2e}, vs the 16-bit product {so.rel_l1(got8, got):.2e}",
+          flush=True)
+    assert err8 <= 2e-3
 
-@pytest.mark.parametrize("causal,dtype,d", [(False, "bf16", 128), (True, "fp16", 64)])
-def test_long_list_two_stage_kernel(sp, causal, dtype, d):
+
+@pytest.mark.parametrize("causal,dtype,d,pv_fp8", [(False, "bf16", 128, False), (True, "fp16", 64, False),
+                                                   (False, "fp16", 128, True), (True, "bf16", 64, True)])
+def test_long_list_two_stage_kernel(sp, causal, dtype, d, pv_fp8):
     """T_n > 1024 selects the kernel variant with two LDS stages and the long tile list: N = 70 000
     (ragged: last Q block 112 rows, last K block 48 keys), one head, a random block mask with a forced
     first column (and diagonal when causal); the output rows of a few Q blocks against the oracle loop."""
@@ -120,18 +138,19 @@ def test_long_list_two_stage_kernel(sp, causal, dtype, d):
         mask_np[0, 0, np.arange(Tm), np.minimum(2 * np.arange(Tm), Tn - 1)] = 1
     mask_np[0, 0, -1, -1] = 1   # the partial last key block is used by the ragged last Q block
     mask_t = torch.from_numpy(mask_np).to("cuda")
-    O, stats = sp.sparge_attn(Q, K, V, mask_t, w.lam, causal=causal, return_stats=True)
+    O, stats = sp.sparge_attn(Q, K, V, mask_t, w.lam, causal=causal, return_stats=True, pv_fp8=pv_fp8)
     torch.cuda.synchronize()
     assert torch.isfinite(O.float()).all()
     q, k, v = x["q"][0, 0], x["k"][0, 0], x["v"][0, 0]
     blocks = [0, 1, Tm // 3, Tm - 2, Tm - 1]
-    ref = so.sparse_attention(q, k, v, mask_np[0, 0], lam=f32(w.lam), causal=causal, quant=True, pv_dtype=dtype,
-                              q_blocks=blocks, ref_slack=REF_SLACK)
+    ref = so.sparse_attention(q, k, v, mask_np[0, 0], lam=f32(w.lam), causal=causal, quant=True,
+                              pv_dtype="fp8e4m3" if pv_fp8 else dtype, q_blocks=blocks,
+                              ref_slack=sp.REF_SLACK_LOG2_FP8 * math.log(2.0) if pv_fp8 else REF_SLACK)
     assert ref.zero_rows == 0
     rows = np.concatenate([np.arange(128 * i, min(128 * (i + 1), N)) for i in blocks])
     got = O[0, 0].float().cpu().numpy().astype(np.float64)[rows]
     err = so.rel_l1(got, so.round16(ref.O[rows], dtype))
-    print(f"  long list causal={causal}: rel-L1 vs oracle {err:.2e}", flush=True)
+    print(f"  long list causal={causal} fp8={pv_fp8}: rel-L1 vs oracle {err:.2e}", flush=True)
     assert err <= 2e-3
     tiles, groups = closed_form_valid(N, causal)
     s = stats.cpu().numpy()[0, 0]
