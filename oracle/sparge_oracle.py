@@ -492,3 +492,70 @@ def spargeattn(Q: np.ndarray, K: np.ndarray, V: np.ndarray, tau: float, theta: f
     pred = predict(Q, K, tau, theta, scale, causal)
     res = sparse_attention(Q, K, V, pred.mask, lam, scale, causal, quant, pv_dtype, ref_slack=ref_slack)
     return res, pred
+
+
+# ----------------------------------------------------------------------------------------------
+# Hyper-parameter determination for one head (Sec. 3.6)
+# ----------------------------------------------------------------------------------------------
+@dataclass
+class TuneResult:
+    tau: float
+    theta: float
+    lam: float               # -inf: no value of the lambda grid was admissible, stage 2 stays off
+    sparsity: float          # mean over the inputs, with (tau, theta, lam)
+    l1: float                # worst input's relative L1 against full attention, with (tau, theta, lam)
+    stage1: np.ndarray       # [n_tau, n_theta, 2]: mean sparsity, worst relative L1 of every (tau, theta)
+    stage2: np.ndarray       # [n_lambda, 2]: the same for every lambda at the chosen (tau, theta)
+
+
+def tune_head(inputs: Sequence[Tuple[np.ndarray, np.ndarray, np.ndarray]], tau_grid: Sequence[float],
+              theta_grid: Sequence[float], lam_grid: Sequence[float], l1: float, l2: float,
+              causal: bool = False, scale: Optional[float] = None, pv_dtype: str = "none",
+              ref_slack: float = 0.0) -> TuneResult:
+    """Sec. 3.6 for one attention head and a handful of inputs (Q, K, V).
+
+    The error of a setting is L1 = sum|O - O'| / sum|O| with O the full attention computed the same way
+    (same quantization and rounding, every block kept, nothing skipped) and O' the sparse one.
+    First the (tau, theta) grid with stage 2 off: among the pairs whose L1 stays below l1 on every
+    input, the one with the largest sparsity (mean over the inputs).  Then the lambda grid at that pair:
+    among the values whose L1 stays below l2 on every input, the one with the largest sparsity, if
+    that beats leaving stage 2 off.
+    Readings (the paper says "constrain the error across five inputs" and no more): the constraint
+    binds the worst input, the objective is the mean; ties keep the earlier grid entry (tau outer,
+    theta inner); if no pair is admissible the pair with the smallest worst-input L1 is taken.
+    Outputs are compared after rounding to pv_dtype when that is a 16-bit type (what a kernel stores).
+    """
+    def out(res):
+        return round16(res.O, pv_dtype) if pv_dtype in ("fp16", "bf16") else res.O
+
+    refs = [out(sparse_attention(Q, K, V, None, -np.inf, scale, causal, True, pv_dtype, ref_slack=ref_slack))
+            for (Q, K, V) in inputs]
+
+    def evaluate(tau, theta, lam):
+        sp, err = [], []
+        for (Q, K, V), ref in zip(inputs, refs):
+            res, _ = spargeattn(Q, K, V, tau, theta, lam, causal, scale, True, pv_dtype, ref_slack)
+            sp.append(res.sparsity)
+            err.append(rel_l1(out(res), ref))
+        return float(np.mean(sp)), float(np.max(err))
+
+    stage1 = np.zeros((len(tau_grid), len(theta_grid), 2))
+    for a, tau in enumerate(tau_grid):
+        for b, theta in enumerate(theta_grid):
+            stage1[a, b] = evaluate(tau, theta, -np.inf)
+    flat = stage1.reshape(-1, 2)
+    ok = flat[:, 1] < l1
+    if ok.any():
+        best = int(np.flatnonzero(ok)[np.argmax(flat[ok, 0])])     # argmax keeps the first of equals
+    else:
+        best = int(np.argmin(flat[:, 1]))
+    a, b = divmod(best, len(theta_grid))
+    tau, theta = tau_grid[a], theta_grid[b]
+    sparsity, err = flat[best]
+    lam = -np.inf
+    stage2 = np.zeros((len(lam_grid), 2))
+    for c, cand in enumerate(lam_grid):
+        stage2[c] = evaluate(tau, theta, cand)
+        if stage2[c, 1] < l2 and stage2[c, 0] > sparsity:
+            lam, (sparsity, err) = cand, stage2[c]
+    return TuneResult(float(tau), float(theta), float(lam), float(sparsity), float(err), stage1, stage2)

@@ -659,3 +659,58 @@ def test_fp8_product_error_is_a_few_percent_and_above_the_16_bit_one():
     ones = so.sparse_attention(Q, K, np.ones_like(V), None, quant=False, pv_dtype="fp8e4m3",
                                ref_slack=2 * math.log(2.0)).O
     assert 0 < np.abs(ones - 1.0).max() < 2.0 ** -4
+
+
+# ------------------------------------------------------------------ hyper-parameter search (Sec. 3.6)
+def _tune_inputs(n=2, N=384, d=32):
+    return [_peaky_inputs(80 + i, N=N, d=d) for i in range(n)]
+
+
+def test_tuner_choice_is_admissible_and_no_admissible_setting_is_sparser():
+    inputs = _tune_inputs()
+    taus, thetas, lams = [0.5, 0.8, 0.95], [-1.0, 0.3, 0.9], [-12.0, -6.0, -3.0]
+    l1, l2 = 0.06, 0.08
+    t = so.tune_head(inputs, taus, thetas, lams, l1, l2)
+    # an independent sweep: full attention by the textbook formula on the dequantized operands
+    def sweep(tau, theta, lam):
+        sp, err = [], []
+        for Q, K, V in inputs:
+            Qd, Kd = so.dequantized_qk(Q, K)
+            full = so.dense_attention(Qd, Kd, V)
+            res, _ = so.spargeattn(Q, K, V, tau, theta, lam)
+            sp.append(res.sparsity)
+            err.append(np.abs(res.O - full).sum() / np.abs(full).sum())
+        return np.mean(sp), np.max(err)
+    table = {(a, b): sweep(a, b, -np.inf) for a in taus for b in thetas}
+    admissible = {k: v for k, v in table.items() if v[1] < l1}
+    assert admissible, "thresholds of this test must leave something admissible"
+    s1, e1 = table[(t.tau, t.theta)]
+    assert e1 < l1 and s1 == pytest.approx(max(v[0] for v in admissible.values()), abs=1e-12)
+    np.testing.assert_allclose(t.stage1.reshape(-1, 2), [table[(a, b)] for a in taus for b in thetas], atol=1e-9)
+    # stage 2 never lowers the sparsity, respects l2, and is the best admissible lambda
+    lam_table = {c: sweep(t.tau, t.theta, c) for c in lams}
+    adm2 = {c: v for c, v in lam_table.items() if v[1] < l2 and v[0] > s1}
+    if adm2:
+        assert t.lam in adm2 and t.sparsity == pytest.approx(max(v[0] for v in adm2.values()), abs=1e-12)
+        assert t.l1 < l2
+    else:
+        assert t.lam == -np.inf and t.sparsity == pytest.approx(s1, abs=1e-12)
+    assert t.sparsity >= s1 - 1e-12
+
+
+def test_tuner_limits():
+    inputs = _tune_inputs(n=2)
+    taus, thetas, lams = [0.6, 0.9], [0.0, 0.5], [-8.0, -2.0]
+    loose = so.tune_head(inputs, taus, thetas, lams, 10.0, 10.0)
+    # every setting is admissible: the sparsest pair of the table and the sparsest lambda win
+    assert loose.stage1[..., 0].max() == pytest.approx(loose.stage1[taus.index(loose.tau), thetas.index(loose.theta), 0])
+    assert loose.sparsity == pytest.approx(max(loose.stage2[:, 0].max(), loose.stage1[..., 0].max()))
+    tight = so.tune_head(inputs, taus, thetas, lams, 0.0, 0.0)
+    # nothing is admissible: the most accurate pair, stage 2 off
+    assert tight.lam == -np.inf
+    assert tight.l1 == pytest.approx(tight.stage1[..., 1].min())
+    mid = so.tune_head(inputs, taus, thetas, lams, 0.05, 0.05)
+    assert tight.sparsity - 1e-12 <= mid.sparsity <= loose.sparsity + 1e-12
+    # a single-entry grid with tau = 1, theta > 1 is full attention: zero error, zero sparsity
+    one = so.tune_head(inputs, [1.0], [2.0], [], 0.01, 0.01)
+    assert one.sparsity == 0.0 and one.l1 == 0.0
