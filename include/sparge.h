@@ -159,6 +159,39 @@ int sparge_forward(const void* Q, const void* K, const void* V, const sparge_des
                    void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
+ * Relative L1 distance of Sec. 3.6, L1 = sum|O - O'| / sum|O| with O the reference: per (batch, head)
+ * the two sums.  O, O_ref: 16-bit tensors laid out as desc says; out: device fp64 [B,H,2] =
+ * {sum|O_ref - O|, sum|O_ref|}, overwritten.
+ */
+int sparge_rel_l1(const void* O, const void* O_ref, const sparge_desc* desc, double* out /* device */,
+                  void* hip_stream);
+
+/*
+ * Hyper-parameter determination for one attention layer (Sec. 3.6), per head, from n_inputs inputs of
+ * one shape.  The error of a setting on an input is the relative L1 distance between the sparse output
+ * and the full attention computed by the same kernels (every block kept, nothing skipped).
+ *   1. every (tau, theta) of the grid with the lambda test off: among the pairs whose error stays
+ *      below l1 on every input, the one with the largest sparsity (mean over the inputs);
+ *   2. every lambda of the grid at the head's chosen pair: among the values whose error stays below l2
+ *      on every input, the one with the largest sparsity, if that beats leaving the test off.
+ * The paper leaves open how five inputs "constrain" the error: here the worst input binds and the mean
+ * sparsity is maximized; ties keep the earlier grid entry (tau outer, theta inner); if no pair is
+ * admissible the pair with the smallest worst-input error is taken.
+ * Q, K, V: host arrays of n_inputs device pointers.  Grids and results are host arrays.  Results:
+ * tau, theta, lambda [H] (lambda = -INFINITY: stage 2 stays off); optional sparsity, l1_out [H] of the
+ * chosen setting; optional tables stage1 [n_tau,n_theta,H,2] and stage2 [n_lambda,H,2] = {mean
+ * sparsity, worst error}.  pv_dtype of desc selects the P~V product that is tuned.
+ * This is the one entry point that synchronises: it reads counters back after every candidate, and it
+ * blocks until the stream has finished.  Workspace: sparge_tune_workspace_bytes (256-byte aligned).
+ */
+int sparge_tune_workspace_bytes(const sparge_desc* desc, int n_inputs, size_t* bytes /* host, out */);
+int sparge_tune(const void* const* Q, const void* const* K, const void* const* V, int n_inputs,
+                const sparge_desc* desc, const float* tau_grid, int n_tau, const float* theta_grid, int n_theta,
+                const float* lambda_grid, int n_lambda, float l1, float l2, float sm_scale, int causal,
+                float* tau, float* theta, float* lambda, double* sparsity, double* l1_out,
+                double* stage1, double* stage2, void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
  * Profiling aid (not part of the method).  Hands the library `n` pairs of caller-created hipEvent_t
  * (host arrays of handles).  From then on, every launch of the attention kernel made by the calling
  * thread is bracketed on its stream by hipEventRecord(starts[k]), hipEventRecord(stops[k]), k counting

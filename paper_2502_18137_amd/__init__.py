@@ -15,6 +15,8 @@ from .binding import (  # noqa: F401
     sparge_forward,
     sparge_predict,
     sparge_quantize,
+    sparge_rel_l1,
+    sparge_tune,
     sparge_version,
     sparge_workspace_bytes,
     tensor_from_numpy,

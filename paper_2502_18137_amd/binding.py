@@ -60,6 +60,13 @@ def load_library() -> ctypes.CDLL:
     lib.sparge_v_tiles.argtypes = [vp, dp, vp, vp]
     lib.sparge_v_tiles_bytes.argtypes = [dp, ctypes.POINTER(ctypes.c_size_t)]
     lib.sparge_attn_tiled.argtypes = [vp, vp, vp, vp, vp, dp, vp, f32p, ctypes.c_float, ctypes.c_int, vp, vp, vp]
+    f64p = ctypes.POINTER(ctypes.c_double)
+    lib.sparge_rel_l1.argtypes = [vp, vp, dp, vp, vp]
+    lib.sparge_tune_workspace_bytes.argtypes = [dp, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t)]
+    lib.sparge_tune.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.c_int, dp,
+                                f32p, ctypes.c_int, f32p, ctypes.c_int, f32p, ctypes.c_int,
+                                ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_int,
+                                f32p, f32p, f32p, f64p, f64p, f64p, f64p, vp, ctypes.c_size_t, vp]
     lib.sparge_set_timing_events.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.c_int]
     lib.sparge_set_timing_events.restype = ctypes.c_int
     lib.sparge_attn.argtypes = [vp, vp, vp, dp, vp, f32p, ctypes.c_float, ctypes.c_int, vp, vp, vp,
@@ -67,7 +74,8 @@ def load_library() -> ctypes.CDLL:
     lib.sparge_forward.argtypes = [vp, vp, vp, dp, f32p, f32p, f32p, ctypes.c_float, ctypes.c_int, vp, vp, vp, vp,
                                    ctypes.c_size_t, vp]
     for name in ("sparge_workspace_bytes", "sparge_quantize", "sparge_predict", "sparge_attn_quantized",
-                 "sparge_attn", "sparge_forward", "sparge_v_tiles", "sparge_attn_tiled", "sparge_v_tiles_bytes"):
+                 "sparge_attn", "sparge_forward", "sparge_v_tiles", "sparge_attn_tiled", "sparge_v_tiles_bytes",
+                 "sparge_rel_l1", "sparge_tune_workspace_bytes", "sparge_tune"):
         getattr(lib, name).restype = ctypes.c_int
     _LIB = lib
     return lib
@@ -287,6 +295,44 @@ def sparge_forward(Q, K, V, tau, theta, lam, causal: bool = False, sm_scale: flo
     if return_stats:
         res.append(stats)
     return res[0] if len(res) == 1 else tuple(res)
+
+
+def sparge_rel_l1(O: torch.Tensor, O_ref: torch.Tensor) -> torch.Tensor:
+    """-> fp64 [B,H,2] = {sum|O_ref - O|, sum|O_ref|} (Sec. 3.6); divide to get the relative L1 distance."""
+    _same_layout(O_ref, O)
+    d = _desc(O)
+    out = torch.empty((O.shape[0], O.shape[1], 2), dtype=torch.float64, device=O.device)
+    _check(load_library().sparge_rel_l1(_ptr(O), _ptr(O_ref), ctypes.byref(d), _ptr(out), _stream()))
+    return out
+
+
+def sparge_tune(inputs, tau_grid, theta_grid, lambda_grid, l1: float, l2: float, causal: bool = False,
+                sm_scale: float = 0.0, pv_fp8: bool = False):
+    """Sec. 3.6 per head.  inputs: list of (Q, K, V) of one shape and layout.
+    -> dict(tau, theta, lam [H] lists; sparsity, l1 [H]; stage1 [n_tau,n_theta,H,2], stage2 [n_lambda,H,2] as
+    nested lists of {mean sparsity, worst relative L1}).  Blocks until done."""
+    import numpy as np
+    Q0 = inputs[0][0]
+    for q, k, v in inputs:
+        _same_layout(Q0, q, k, v)
+    d = _desc(Q0, pv_fp8)
+    H, n = Q0.shape[1], len(inputs)
+    need = ctypes.c_size_t(0)
+    _check(load_library().sparge_tune_workspace_bytes(ctypes.byref(d), n, ctypes.byref(need)))
+    ws = torch.empty(need.value, dtype=torch.uint8, device=Q0.device)
+    arr = lambda k: (ctypes.c_void_p * n)(*[t[k].data_ptr() for t in inputs])
+    fl = lambda xs: (ctypes.c_float * len(xs))(*[float(x) for x in xs])
+    tau, theta, lam = (ctypes.c_float * H)(), (ctypes.c_float * H)(), (ctypes.c_float * H)()
+    sp, err = (ctypes.c_double * H)(), (ctypes.c_double * H)()
+    n1, n2 = len(tau_grid) * len(theta_grid), len(lambda_grid)
+    s1, s2 = (ctypes.c_double * (n1 * H * 2))(), (ctypes.c_double * max(n2 * H * 2, 1))()
+    _check(load_library().sparge_tune(arr(0), arr(1), arr(2), n, ctypes.byref(d), fl(tau_grid), len(tau_grid),
+                                      fl(theta_grid), len(theta_grid), fl(lambda_grid), n2, float(l1), float(l2),
+                                      float(sm_scale), int(causal), tau, theta, lam, sp, err, s1, s2, _ptr(ws),
+                                      ws.numel(), _stream()))
+    return {"tau": list(tau), "theta": list(theta), "lam": list(lam), "sparsity": list(sp), "l1": list(err),
+            "stage1": np.array(s1[:]).reshape(len(tau_grid), len(theta_grid), H, 2),
+            "stage2": np.array(s2[:n2 * H * 2]).reshape(n2, H, 2)}
 
 
 class AttnKernelTimer:

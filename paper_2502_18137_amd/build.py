@@ -23,6 +23,7 @@ SOURCES = {
     "predict.hip": ["-ffp-contract=off"],
     "attn.hip": [],
     "v_fp8.hip": ["-ffp-contract=off"],
+    "metrics.hip": ["-ffp-contract=off"],
     "api.hip": [],
 }
 

@@ -4,6 +4,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <vector>
 
 #include "common.hpp"
 
@@ -357,6 +358,191 @@ int sparge_forward(const void* Q, const void* K, const void* V, const sparge_des
     if ((rc = run_predict(s, ws, w, t, th, sm_scale, causal, mask, st))) return rc;
     return run_attn(at<int8_t>(ws, w.Qq), at<int8_t>(ws, w.Kq), at<float>(ws, w.q_scale), at<float>(ws, w.k_scale),
                     V, s, at<char>(ws, w.v_tiles), mask, lam, sm_scale, causal, O, stats, st);
+}
+
+int sparge_rel_l1(const void* O, const void* O_ref, const sparge_desc* desc, double* out, void* hip_stream) {
+    Shape s;
+    int rc = check_desc(desc, &s);
+    if (rc) return rc;
+    if (!O || !O_ref || !out) return fail(SPARGE_EINVAL, "NULL tensor argument");
+    if (misaligned(O) || misaligned(O_ref)) return fail(SPARGE_EINVAL, "tensor pointers must be 16-byte aligned");
+    hipError_t e = launch_rel_l1(O, O_ref, s, out, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? SPARGE_OK : hip_fail(e, "rel_l1");
+}
+
+namespace {
+
+// Workspace of the hyper-parameter search: per input a forward workspace and the full-attention output,
+// then one output buffer, the error sums and the counters.
+struct TuneWs {
+    size_t fwd_bytes, out_bytes, per_input, o_cur, metrics, stats, total;
+};
+TuneWs tune_layout(const Shape& s, int n_inputs) {
+    TuneWs t{};
+    t.fwd_bytes = align256(plan(s, SPARGE_WS_FORWARD).total);
+    const size_t span = (size_t)(s.B - 1) * s.sb + (size_t)(s.H - 1) * s.sh + (size_t)(s.N - 1) * s.sn + s.d;
+    t.out_bytes = align256(span * sizeof(uint16_t));
+    t.per_input = t.fwd_bytes + t.out_bytes;
+    t.o_cur = t.per_input * n_inputs;
+    t.metrics = t.o_cur + t.out_bytes;
+    t.stats = t.metrics + align256((size_t)s.B * s.H * 2 * sizeof(double));
+    t.total = t.stats + align256((size_t)s.B * s.H * 4 * sizeof(uint64_t));
+    return t;
+}
+
+}  // namespace
+
+int sparge_tune_workspace_bytes(const sparge_desc* desc, int n_inputs, size_t* bytes) {
+    Shape s;
+    int rc = check_desc(desc, &s);
+    if (rc) return rc;
+    if (n_inputs < 1 || !bytes) return fail(SPARGE_EINVAL, "n_inputs must be >= 1 and bytes not NULL");
+    *bytes = tune_layout(s, n_inputs).total;
+    return SPARGE_OK;
+}
+
+int sparge_tune(const void* const* Q, const void* const* K, const void* const* V, int n_inputs,
+                const sparge_desc* desc, const float* tau_grid, int n_tau, const float* theta_grid, int n_theta,
+                const float* lambda_grid, int n_lambda, float l1, float l2, float sm_scale, int causal,
+                float* tau, float* theta, float* lambda, double* sparsity, double* l1_out, double* stage1,
+                double* stage2, void* ws, size_t ws_bytes, void* hip_stream) {
+    Shape s;
+    int rc = check_desc(desc, &s);
+    if (rc) return rc;
+    if (n_inputs < 1 || !Q || !K || !V) return fail(SPARGE_EINVAL, "no inputs");
+    if (n_tau < 1 || n_theta < 1 || n_lambda < 0 || !tau_grid || !theta_grid || (n_lambda && !lambda_grid))
+        return fail(SPARGE_EINVAL, "empty tau/theta grid or missing lambda grid");
+    if (!tau || !theta || !lambda) return fail(SPARGE_EINVAL, "result arrays are NULL");
+    for (int n = 0; n < n_inputs; ++n) {
+        if (!Q[n] || !K[n] || !V[n]) return fail(SPARGE_EINVAL, "input %d has a NULL tensor", n);
+        if (misaligned(Q[n]) || misaligned(K[n]) || misaligned(V[n]))
+            return fail(SPARGE_EINVAL, "tensor pointers must be 16-byte aligned");
+    }
+    for (int a = 0; a < n_tau; ++a)
+        if (!(tau_grid[a] > 0.f && tau_grid[a] <= 1.f)) return fail(SPARGE_EINVAL, "tau_grid[%d] outside (0,1]", a);
+    for (int b = 0; b < n_theta; ++b)
+        if (std::isnan(theta_grid[b])) return fail(SPARGE_EINVAL, "theta_grid[%d] is NaN", b);
+    for (int c = 0; c < n_lambda; ++c)
+        if (!(lambda_grid[c] < 0.f)) return fail(SPARGE_EINVAL, "lambda_grid[%d] must be < 0", c);
+    const TuneWs t = tune_layout(s, n_inputs);
+    if (!ws) return fail(SPARGE_EINVAL, "workspace is NULL");
+    if (reinterpret_cast<uintptr_t>(ws) & 255u) return fail(SPARGE_EINVAL, "workspace must be 256-byte aligned");
+    if (ws_bytes < t.total) return fail(SPARGE_ENOSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, t.total);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const Workspace w = plan(s, SPARGE_WS_FORWARD);
+    const int BH = s.B * s.H, H = s.H;
+    auto fwd = [&](int n) { return static_cast<void*>(static_cast<char*>(ws) + t.per_input * n); };
+    auto o_ref = [&](int n) { return static_cast<void*>(static_cast<char*>(ws) + t.per_input * n + t.fwd_bytes); };
+    void* o_cur = at<char>(ws, t.o_cur);
+    double* d_metrics = at<double>(ws, t.metrics);
+    uint64_t* d_stats = at<uint64_t>(ws, t.stats);
+    hipError_t e;
+
+    // per input, once: block statistics, quantization, V tiles, and the full attention it is measured against
+    HeadParams off;
+    std::memset(&off, 0, sizeof(off));
+    for (int h = 0; h < H; ++h) off.v[h] = -INFINITY;
+    for (int n = 0; n < n_inputs; ++n) {
+        void* f = fwd(n);
+        if ((rc = run_stats_and_quant(Q[n], K[n], s, at<double>(f, w.pooled_q), at<double>(f, w.ksum_t),
+                                      at<double>(f, w.sim_q), at<double>(f, w.sim_k), at<int8_t>(f, w.Qq),
+                                      at<float>(f, w.q_scale), at<int8_t>(f, w.Kq), at<float>(f, w.k_scale),
+                                      at<float>(f, w.k_mean), st))) return rc;
+        if ((rc = run_attn(at<int8_t>(f, w.Qq), at<int8_t>(f, w.Kq), at<float>(f, w.q_scale), at<float>(f, w.k_scale),
+                           V[n], s, at<char>(f, w.v_tiles), nullptr, off, sm_scale, causal, o_ref(n), nullptr, st)))
+            return rc;
+    }
+
+    std::vector<double> h_metrics(BH * 2);
+    std::vector<uint64_t> h_stats(BH * 4);
+    // one setting on every input: per head the mean sparsity and the worst relative L1
+    auto evaluate = [&](const HeadParams& tp, const HeadParams& thp, const HeadParams& lp, double* sp, double* err) -> int {
+        for (int h = 0; h < H; ++h) { sp[h] = 0.0; err[h] = 0.0; }
+        for (int n = 0; n < n_inputs; ++n) {
+            void* f = fwd(n);
+            int r;
+            if ((r = run_predict(s, f, w, tp, thp, sm_scale, causal, at<uint8_t>(f, w.mask), st))) return r;
+            if ((r = timed_attn(at<int8_t>(f, w.Qq), at<int8_t>(f, w.Kq), at<float>(f, w.q_scale),
+                                at<float>(f, w.k_scale), at<char>(f, w.v_tiles), s, at<uint8_t>(f, w.mask), lp,
+                                sm_scale, causal, o_cur, d_stats, st))) return r;
+            if ((e = launch_rel_l1(o_cur, o_ref(n), s, d_metrics, st)) != hipSuccess) return hip_fail(e, "rel_l1");
+            if ((e = hipMemcpyAsync(h_metrics.data(), d_metrics, BH * 2 * sizeof(double), hipMemcpyDeviceToHost, st)) != hipSuccess)
+                return hip_fail(e, "copy error sums");
+            if ((e = hipMemcpyAsync(h_stats.data(), d_stats, BH * 4 * sizeof(uint64_t), hipMemcpyDeviceToHost, st)) != hipSuccess)
+                return hip_fail(e, "copy counters");
+            if ((e = hipStreamSynchronize(st)) != hipSuccess) return hip_fail(e, "synchronize");
+            for (int h = 0; h < H; ++h) {
+                double num = 0.0, den = 0.0;
+                uint64_t c[4] = {0, 0, 0, 0};
+                for (int b = 0; b < s.B; ++b) {
+                    num += h_metrics[(b * H + h) * 2 + 0];
+                    den += h_metrics[(b * H + h) * 2 + 1];
+                    for (int q = 0; q < 4; ++q) c[q] += h_stats[(b * H + h) * 4 + q];
+                }
+                sp[h] += 1.0 - 0.5 * ((double)c[0] / (double)c[2] + (double)c[1] / (double)c[3]);
+                err[h] = std::fmax(err[h], num / den);
+            }
+        }
+        for (int h = 0; h < H; ++h) sp[h] /= n_inputs;
+        return SPARGE_OK;
+    };
+
+    // stage 1: the (tau, theta) grid with the lambda test off
+    const int n1 = n_tau * n_theta;
+    std::vector<double> t1((size_t)n1 * H * 2), sp(H), err(H);
+    HeadParams tp, thp, lp;
+    std::memset(&tp, 0, sizeof(tp));
+    std::memset(&thp, 0, sizeof(thp));
+    for (int a = 0; a < n_tau; ++a)
+        for (int b = 0; b < n_theta; ++b) {
+            for (int h = 0; h < H; ++h) { tp.v[h] = tau_grid[a]; thp.v[h] = theta_grid[b]; }
+            if ((rc = evaluate(tp, thp, off, sp.data(), err.data()))) return rc;
+            for (int h = 0; h < H; ++h) {
+                t1[((size_t)(a * n_theta + b) * H + h) * 2 + 0] = sp[h];
+                t1[((size_t)(a * n_theta + b) * H + h) * 2 + 1] = err[h];
+            }
+        }
+    std::vector<double> best_sp(H), best_err(H);
+    for (int h = 0; h < H; ++h) {
+        int best = -1;
+        for (int k = 0; k < n1; ++k) {  // the sparsest admissible pair; the earlier one of equals
+            const double ks = t1[((size_t)k * H + h) * 2], ke = t1[((size_t)k * H + h) * 2 + 1];
+            if (ke < (double)l1 && (best < 0 || ks > t1[((size_t)best * H + h) * 2])) best = k;
+        }
+        if (best < 0) {                 // nothing admissible: the most accurate pair
+            best = 0;
+            for (int k = 1; k < n1; ++k)
+                if (t1[((size_t)k * H + h) * 2 + 1] < t1[((size_t)best * H + h) * 2 + 1]) best = k;
+        }
+        tau[h] = tau_grid[best / n_theta];
+        theta[h] = theta_grid[best % n_theta];
+        lambda[h] = -INFINITY;
+        best_sp[h] = t1[((size_t)best * H + h) * 2];
+        best_err[h] = t1[((size_t)best * H + h) * 2 + 1];
+        tp.v[h] = tau[h];
+        thp.v[h] = theta[h];
+    }
+    if (stage1) std::memcpy(stage1, t1.data(), t1.size() * sizeof(double));
+
+    // stage 2: the lambda grid at each head's own (tau, theta)
+    std::memset(&lp, 0, sizeof(lp));
+    for (int c = 0; c < n_lambda; ++c) {
+        for (int h = 0; h < H; ++h) lp.v[h] = lambda_grid[c];
+        if ((rc = evaluate(tp, thp, lp, sp.data(), err.data()))) return rc;
+        for (int h = 0; h < H; ++h) {
+            if (stage2) { stage2[((size_t)c * H + h) * 2] = sp[h]; stage2[((size_t)c * H + h) * 2 + 1] = err[h]; }
+            if (err[h] < (double)l2 && sp[h] > best_sp[h]) {
+                lambda[h] = lambda_grid[c];
+                best_sp[h] = sp[h];
+                best_err[h] = err[h];
+            }
+        }
+    }
+    for (int h = 0; h < H; ++h) {
+        if (sparsity) sparsity[h] = best_sp[h];
+        if (l1_out) l1_out[h] = best_err[h];
+    }
+    return SPARGE_OK;
 }
 
 int sparge_set_timing_events(void* const* starts, void* const* stops, int n) {

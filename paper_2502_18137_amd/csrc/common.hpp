@@ -89,4 +89,7 @@ hipError_t launch_attn(const int8_t* Qq, const int8_t* Kq, const float* q_scale,
 hipError_t launch_v_tiles_fp8(const void* V, const Shape& s, unsigned char* tiles, float* v_scale,
                               uint32_t* amax_bits, hipStream_t st);
 
+// out[b,h] = {sum|Oref - O|, sum|Oref|} in fp64 (zeroed here), both tensors laid out as the shape says.
+hipError_t launch_rel_l1(const void* O, const void* Oref, const Shape& s, double* out, hipStream_t st);
+
 }  // namespace sparge
