@@ -559,3 +559,61 @@ def tune_head(inputs: Sequence[Tuple[np.ndarray, np.ndarray, np.ndarray]], tau_g
         if stage2[c, 1] < l2 and stage2[c, 0] > sparsity:
             lam, (sparsity, err) = cand, stage2[c]
     return TuneResult(float(tau), float(theta), float(lam), float(sparsity), float(err), stage1, stage2)
+
+
+# ----------------------------------------------------------------------------------------------
+# HilbertCurve permutation (Sec. 3.7): visual tokens of a T x H x W grid flattened along a Hilbert curve
+# ----------------------------------------------------------------------------------------------
+def hilbert_cells(bits: int, ndim: int) -> np.ndarray:
+    """The cells of the 2^bits hyper-cube in the order a Hilbert curve visits them: int64 [2^(bits*ndim), ndim].
+
+    Decoding direction of Skilling's transform ("Programming the Hilbert curve", 2004): the index's
+    bits are dealt out to the axes (most significant bit to axis 0), the Gray code is undone, and
+    from the second-finest level upwards the low bits of axis 0 and axis i are exchanged or inverted.
+    """
+    total = 1 << (bits * ndim)
+    h = np.arange(total, dtype=np.int64)
+    X = [np.zeros(total, dtype=np.int64) for _ in range(ndim)]
+    for pos in range(bits * ndim):                    # pos counts index bits from the most significant one
+        bit = (h >> (bits * ndim - 1 - pos)) & 1
+        X[pos % ndim] |= bit << (bits - 1 - pos // ndim)
+    top = 2 << (bits - 1)
+    t = X[ndim - 1] >> 1                              # Gray decode
+    for i in range(ndim - 1, 0, -1):
+        X[i] ^= X[i - 1]
+    X[0] ^= t
+    q = 2
+    while q != top:                                   # undo the exchanges, coarse levels last
+        p = q - 1
+        for i in range(ndim - 1, -1, -1):
+            hit = (X[i] & q) != 0
+            if i == 0:
+                X[0] = np.where(hit, X[0] ^ p, X[0])
+            else:
+                swap = (X[0] ^ X[i]) & p
+                X[0], X[i] = np.where(hit, X[0] ^ p, X[0] ^ swap), np.where(hit, X[i], X[i] ^ swap)
+        q <<= 1
+    return np.stack(X, axis=1)
+
+
+def hilbert_order(grid: Sequence[int]) -> np.ndarray:
+    """Permutation p: sequence position s holds the row-major cell p[s] of the grid (T, H, W).
+    The curve fills the enclosing 2^b cube; cells outside the grid are skipped."""
+    grid = tuple(int(g) for g in grid)
+    bits = max(1, int(math.ceil(math.log2(max(grid)))))
+    cells = hilbert_cells(bits, len(grid))
+    inside = np.all(cells < np.array(grid)[None, :], axis=1)
+    cells = cells[inside]
+    return np.ravel_multi_index(tuple(cells[:, i] for i in range(len(grid))), grid).astype(np.int64)
+
+
+def permute_tokens(X: np.ndarray, perm: np.ndarray, offset: int = 0, inverse: bool = False) -> np.ndarray:
+    """Y[offset + s] = X[offset + perm[s]] (inverse: Y[offset + perm[s]] = X[offset + s]); tokens outside
+    [offset, offset + len(perm)) keep their place (App. A: only the visual tokens are permuted)."""
+    Y = np.array(X, copy=True)
+    L = len(perm)
+    if inverse:
+        Y[offset + np.asarray(perm)] = X[offset:offset + L]
+    else:
+        Y[offset:offset + L] = X[offset + np.asarray(perm)]
+    return Y

@@ -714,3 +714,51 @@ def test_tuner_limits():
     # a single-entry grid with tau = 1, theta > 1 is full attention: zero error, zero sparsity
     one = so.tune_head(inputs, [1.0], [2.0], [], 0.01, 0.01)
     assert one.sparsity == 0.0 and one.l1 == 0.0
+
+
+# ------------------------------------------------------------------ HilbertCurve permutation (Sec. 3.7)
+@pytest.mark.parametrize("bits,ndim", [(1, 2), (2, 2), (4, 2), (1, 3), (2, 3), (4, 3)])
+def test_hilbert_curve_is_a_continuous_space_filling_walk(bits, ndim):
+    c = so.hilbert_cells(bits, ndim)
+    side = 1 << bits
+    assert c.shape == (side ** ndim, ndim) and c.min() == 0 and c.max() == side - 1
+    assert len({tuple(x) for x in c}) == len(c)                          # every cell once
+    assert (np.abs(np.diff(c, axis=0)).sum(axis=1) == 1).all()           # neighbours along the curve touch
+    assert not c[0].any()                                                # starts in the corner at the origin
+    assert sorted(c[-1].tolist()) == [0] * (ndim - 1) + [side - 1]       # ends in the corner one edge away
+    if bits > 1:
+        # self-similarity: each 2^-ndim part of the curve fills one half-size sub-cube
+        part = len(c) >> ndim
+        for k in range(1 << ndim):
+            sub = c[k * part:(k + 1) * part] >> (bits - 1)
+            assert (sub == sub[0]).all()
+
+
+def test_hilbert_order_of_a_grid_and_the_generators_encoder():
+    from synth import hilbert_order as encode_side   # index computed per cell, then sorted: the other direction
+    for grid in [(1, 6, 6), (3, 5, 7), (13, 30, 45), (8, 8), (2, 1, 3)]:
+        p = so.hilbert_order(grid)
+        assert sorted(p.tolist()) == list(range(int(np.prod(grid))))
+        np.testing.assert_array_equal(p, encode_side(grid))
+    # on a power-of-two grid consecutive tokens are grid neighbours
+    p = so.hilbert_order((4, 8, 8))
+    cells = np.stack(np.unravel_index(p[:], (4, 8, 8)), axis=1)
+    # the enclosing cube is 8^3; inside the 4x8x8 slab the walk may leave and re-enter, but never jumps far on average
+    assert np.abs(np.diff(cells, axis=0)).sum(axis=1).mean() < 1.5
+
+
+def test_token_permutation_round_trip_and_attention_invariance():
+    r = rng(90)
+    N, d, off = 200, 16, 30
+    perm = so.hilbert_order((2, 5, 9))                    # 90 visual tokens after 30 text tokens; 80 more behind
+    X = r.standard_normal((N, d))
+    Y = so.permute_tokens(X, perm, off)
+    np.testing.assert_array_equal(Y[:off], X[:off])
+    np.testing.assert_array_equal(Y[off + len(perm):], X[off + len(perm):])
+    np.testing.assert_array_equal(Y[off + 7], X[off + perm[7]])
+    np.testing.assert_array_equal(so.permute_tokens(Y, perm, off, inverse=True), X)
+    # attention is invariant: permute Q, K, V alike, attend, un-permute the output (Sec. 3.7)
+    Q, K, V = (r.standard_normal((N, d)) for _ in range(3))
+    O = so.dense_attention(Q, K, V)
+    Op = so.dense_attention(*(so.permute_tokens(T, perm, off) for T in (Q, K, V)))
+    np.testing.assert_allclose(so.permute_tokens(Op, perm, off, inverse=True), O, rtol=0, atol=1e-12)
