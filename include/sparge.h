@@ -192,6 +192,21 @@ int sparge_tune(const void* const* Q, const void* const* K, const void* const* V
                 double* stage1, double* stage2, void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
+ * HilbertCurve permutation (Sec. 3.7; App. A).  sparge_hilbert_order: perm[s] = row-major index (t, h, w
+ * with w fastest) of the s-th cell a Hilbert curve visits in a T x H x W grid; the curve fills the
+ * enclosing 2^b cube (b = ceil(log2(max(T, H, W))), at least 1) and cells outside the grid are skipped;
+ * T = 1 (a single frame, an image) selects the two-dimensional curve over (H, W).
+ * Host function, perm: host int32 [T*H*W].
+ * sparge_permute_tokens: dst[b,h,offset + s,:] = src[b,h,offset + perm[s],:] for s < L (inverse != 0:
+ * dst[b,h,offset + perm[s],:] = src[b,h,offset + s,:]); tokens outside [offset, offset + L) are copied in
+ * place (joint text-visual attention permutes the visual tokens only).  perm: device int32 [L], a
+ * permutation of 0..L-1 (an entry outside that range leaves its token in place; duplicates are not detected).  src, dst: distinct 16-bit tensors laid out as desc says.
+ */
+int sparge_hilbert_order(int T, int H, int W, int32_t* perm /* host, out */);
+int sparge_permute_tokens(const void* src, const sparge_desc* desc, const int32_t* perm /* device */, int L,
+                          int offset, int inverse, void* dst, void* hip_stream);
+
+/*
  * Profiling aid (not part of the method).  Hands the library `n` pairs of caller-created hipEvent_t
  * (host arrays of handles).  From then on, every launch of the attention kernel made by the calling
  * thread is bracketed on its stream by hipEventRecord(starts[k]), hipEventRecord(stops[k]), k counting

@@ -14,6 +14,8 @@ from .binding import (  # noqa: F401
     sparge_v_tiles,
     sparge_forward,
     sparge_predict,
+    sparge_hilbert_order,
+    sparge_permute_tokens,
     sparge_quantize,
     sparge_rel_l1,
     sparge_tune,

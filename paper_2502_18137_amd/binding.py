@@ -67,6 +67,8 @@ def load_library() -> ctypes.CDLL:
                                 f32p, ctypes.c_int, f32p, ctypes.c_int, f32p, ctypes.c_int,
                                 ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_int,
                                 f32p, f32p, f32p, f64p, f64p, f64p, f64p, vp, ctypes.c_size_t, vp]
+    lib.sparge_hilbert_order.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_int32)]
+    lib.sparge_permute_tokens.argtypes = [vp, dp, vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp]
     lib.sparge_set_timing_events.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.c_int]
     lib.sparge_set_timing_events.restype = ctypes.c_int
     lib.sparge_attn.argtypes = [vp, vp, vp, dp, vp, f32p, ctypes.c_float, ctypes.c_int, vp, vp, vp,
@@ -75,7 +77,8 @@ def load_library() -> ctypes.CDLL:
                                    ctypes.c_size_t, vp]
     for name in ("sparge_workspace_bytes", "sparge_quantize", "sparge_predict", "sparge_attn_quantized",
                  "sparge_attn", "sparge_forward", "sparge_v_tiles", "sparge_attn_tiled", "sparge_v_tiles_bytes",
-                 "sparge_rel_l1", "sparge_tune_workspace_bytes", "sparge_tune"):
+                 "sparge_rel_l1", "sparge_tune_workspace_bytes", "sparge_tune", "sparge_hilbert_order",
+                 "sparge_permute_tokens"):
         getattr(lib, name).restype = ctypes.c_int
     _LIB = lib
     return lib
@@ -333,6 +336,28 @@ def sparge_tune(inputs, tau_grid, theta_grid, lambda_grid, l1: float, l2: float,
     return {"tau": list(tau), "theta": list(theta), "lam": list(lam), "sparsity": list(sp), "l1": list(err),
             "stage1": np.array(s1[:]).reshape(len(tau_grid), len(theta_grid), H, 2),
             "stage2": np.array(s2[:n2 * H * 2]).reshape(n2, H, 2)}
+
+
+def sparge_hilbert_order(T: int, H: int, W: int) -> torch.Tensor:
+    """-> int32 [T*H*W] (CPU tensor): the row-major grid cell at every position along the Hilbert curve (Sec. 3.7)."""
+    n = T * H * W
+    buf = (ctypes.c_int32 * n)()
+    _check(load_library().sparge_hilbert_order(T, H, W, buf))
+    return torch.frombuffer(buf, dtype=torch.int32).clone()
+
+
+def sparge_permute_tokens(x: torch.Tensor, perm: torch.Tensor, offset: int = 0, inverse: bool = False,
+                          out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Gathers tokens [offset, offset + len(perm)) of a [B,H,N,d] tensor by `perm` (device int32), or scatters
+    them back (inverse); the other tokens are copied."""
+    if perm.dtype != torch.int32 or not perm.is_cuda or not perm.is_contiguous() or perm.dim() != 1:
+        raise SpargeError("perm must be a contiguous int32 vector on the GPU")
+    d = _desc(x)
+    y = torch.empty_like(x) if out is None else out
+    _same_layout(x, y)
+    _check(load_library().sparge_permute_tokens(_ptr(x), ctypes.byref(d), _ptr(perm), perm.numel(), int(offset),
+                                                int(inverse), _ptr(y), _stream()))
+    return y
 
 
 class AttnKernelTimer:

@@ -24,6 +24,7 @@ SOURCES = {
     "attn.hip": [],
     "v_fp8.hip": ["-ffp-contract=off"],
     "metrics.hip": ["-ffp-contract=off"],
+    "permute.hip": [],
     "api.hip": [],
 }
 

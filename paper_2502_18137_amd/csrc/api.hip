@@ -545,6 +545,29 @@ int sparge_tune(const void* const* Q, const void* const* K, const void* const* V
     return SPARGE_OK;
 }
 
+int sparge_hilbert_order(int T, int H, int W, int32_t* perm) {
+    if (T < 1 || H < 1 || W < 1) return fail(SPARGE_EINVAL, "grid dimensions must be >= 1 (got %d, %d, %d)", T, H, W);
+    if (T > 1024 || H > 1024 || W > 1024 || (long long)T * H * W > (1ll << 30))
+        return fail(SPARGE_EUNSUPPORTED, "grid %d x %d x %d too large", T, H, W);
+    if (!perm) return fail(SPARGE_EINVAL, "perm is NULL");
+    hilbert_order_host(T, H, W, perm);
+    return SPARGE_OK;
+}
+
+int sparge_permute_tokens(const void* src, const sparge_desc* desc, const int32_t* perm, int L, int offset,
+                          int inverse, void* dst, void* hip_stream) {
+    Shape s;
+    int rc = check_desc(desc, &s);
+    if (rc) return rc;
+    if (!src || !dst || !perm) return fail(SPARGE_EINVAL, "NULL tensor argument");
+    if (src == dst) return fail(SPARGE_EINVAL, "src and dst must not be the same tensor");
+    if (misaligned(src) || misaligned(dst)) return fail(SPARGE_EINVAL, "tensor pointers must be 16-byte aligned");
+    if (L < 0 || offset < 0 || (long long)offset + L > s.N)
+        return fail(SPARGE_EINVAL, "tokens [%d, %d) do not lie inside N = %d", offset, offset + L, s.N);
+    hipError_t e = launch_permute_tokens(src, s, perm, L, offset, inverse, dst, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? SPARGE_OK : hip_fail(e, "permute_tokens");
+}
+
 int sparge_set_timing_events(void* const* starts, void* const* stops, int n) {
     if (n < 0) return fail(SPARGE_EINVAL, "n must be >= 0");
     if (n > 0 && (!starts || !stops)) return fail(SPARGE_EINVAL, "event arrays are NULL");

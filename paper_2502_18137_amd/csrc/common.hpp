@@ -92,4 +92,10 @@ hipError_t launch_v_tiles_fp8(const void* V, const Shape& s, unsigned char* tile
 // out[b,h] = {sum|Oref - O|, sum|Oref|} in fp64 (zeroed here), both tensors laid out as the shape says.
 hipError_t launch_rel_l1(const void* O, const void* Oref, const Shape& s, double* out, hipStream_t st);
 
+// Order in which a Hilbert curve visits the row-major cells of a T x H x W grid (host; perm has T*H*W entries).
+void hilbert_order_host(int T, int H, int W, int32_t* perm);
+// Token gather by that order, or its inverse, on [off, off + L); other tokens are copied in place.
+hipError_t launch_permute_tokens(const void* src, const Shape& s, const int32_t* perm, int L, int off, int inverse,
+                                 void* dst, hipStream_t st);
+
 }  // namespace sparge
