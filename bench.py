@@ -87,7 +87,7 @@ def event_time(fn, reps=5, warmup=2):
     return float(np.median(out))
 
 
-def run_workload(w, data, steps, warmup, detail=True, pv_fp8=False):
+def run_workload(w, data, steps, warmup, detail=True, pv_fp8=False, qk16=False):
     import torch
     import paper_2502_18137_amd as sp
 
@@ -97,11 +97,11 @@ def run_workload(w, data, steps, warmup, detail=True, pv_fp8=False):
     mask = torch.empty((w.B, w.H, (w.N + 127) // 128, (w.N + 63) // 64), dtype=torch.uint8, device="cuda")
 
     def step():
-        sp.sparge_forward(Q, K, V, w.tau, w.theta, w.lam, causal=w.causal, ws=ws, out=O, pv_fp8=pv_fp8)
+        sp.sparge_forward(Q, K, V, w.tau, w.theta, w.lam, causal=w.causal, ws=ws, out=O, pv_fp8=pv_fp8, qk16=qk16)
 
     # one instrumented pass for the counters and the mask
     _, mask, stats = sp.sparge_forward(Q, K, V, w.tau, w.theta, w.lam, causal=w.causal, ws=ws, out=O,
-                                       return_mask=True, return_stats=True, pv_fp8=pv_fp8)
+                                       return_mask=True, return_stats=True, pv_fp8=pv_fp8, qk16=qk16)
     torch.cuda.synchronize()
     stats = stats.cpu().numpy()
 
@@ -120,7 +120,7 @@ def run_workload(w, data, steps, warmup, detail=True, pv_fp8=False):
     attn_ms = float(np.mean(attn_ms_list))
 
     qk_ops, pv_flops = executed_ops(stats, w.d)
-    ideal_s = qk_ops / PEAK_INT8 + pv_flops / (PEAK_FP8 if pv_fp8 else PEAK_16)
+    ideal_s = qk_ops / (PEAK_16 if qk16 else PEAK_INT8) + pv_flops / (PEAK_FP8 if pv_fp8 else PEAK_16)
     total = qk_ops + pv_flops
     res = {
         "ms_per_step": ms_step,
@@ -135,12 +135,12 @@ def run_workload(w, data, steps, warmup, detail=True, pv_fp8=False):
             "peak": total / ideal_s / 1e12,
             "unit": "TFLOP/s",
             "frac": ideal_s / (attn_ms * 1e-3),
-            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if w.H == CONFIGS_H.get(w.name) and not pv_fp8 else None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if w.H == CONFIGS_H.get(w.name) and not pv_fp8 and not qk16 else None,
             "traffic_unit": "bytes per launch (HBM side of L2, rocprofv3 FETCH_SIZE + WRITE_SIZE)",
             "executed_int8_ops": qk_ops, "executed_16bit_flops": pv_flops,
         },
     }
-    if detail and not pv_fp8:
+    if detail and not pv_fp8 and not qk16:
         wsq = torch.empty(sp.sparge_workspace_bytes(Q, sp.WS_QUANTIZE), dtype=torch.uint8, device="cuda")
         wsp = torch.empty(sp.sparge_workspace_bytes(Q, sp.WS_PREDICT), dtype=torch.uint8, device="cuda")
         res["quantize_ms"] = event_time(lambda: sp.sparge_quantize(Q, K, ws=wsq))
@@ -212,6 +212,7 @@ def sweep_sparsity(steps):
     Qq, Kq, qs, ks, _ = sp.sparge_quantize(Q, K)
     vt = sp.sparge_v_tiles(V)
     vt8 = sp.sparge_v_tiles(V, pv_fp8=True)
+    ws16 = torch.empty(sp.sparge_workspace_bytes(Q, sp.WS_ATTN), dtype=torch.uint8, device="cuda")
     O = torch.empty_like(V)
     Tm, Tn = (N + 127) // 128, (N + 63) // 64
     ops = 4.0 * N * N * d * H
@@ -229,8 +230,12 @@ def sweep_sparsity(steps):
         rows.append({"sparsity": sparsity_of(st), "attn_ms": ms, "dense_equiv_tops": ops / (ms * 1e-3) / 1e12,
                      "mfma_frac": (qk_ops / PEAK_INT8 + pv_flops / PEAK_16) / (ms * 1e-3),
                      "fp8_pv_attn_ms": ms8, "fp8_pv_dense_equiv_tops": ops / (ms8 * 1e-3) / 1e12})
+        # the unquantized variant goes through sparge_attn: its time includes re-tiling V (about 2 % at density 1)
+        ms16 = event_time(lambda: sp.sparge_attn(Q, K, V, mask, -math.inf, ws=ws16, out=O, qk16=True), reps=steps, warmup=2)
+        rows[-1].update({"qk16_attn_ms": ms16, "qk16_dense_equiv_tops": ops / (ms16 * 1e-3) / 1e12})
         log(f"  sparsity {rows[-1]['sparsity']:.2f}: {ms:.3f} ms, {rows[-1]['dense_equiv_tops']:.0f} dense-equivalent TOPS, "
-            f"MFMA frac {rows[-1]['mfma_frac']:.3f}; FP8 P~V {ms8:.3f} ms, {rows[-1]['fp8_pv_dense_equiv_tops']:.0f} TOPS")
+            f"MFMA frac {rows[-1]['mfma_frac']:.3f}; FP8 P~V {ms8:.3f} ms, {rows[-1]['fp8_pv_dense_equiv_tops']:.0f} TOPS; "
+            f"16-bit Q K^T {ms16:.3f} ms, {rows[-1]['qk16_dense_equiv_tops']:.0f} TOPS")
     return {"sweep": "sparsity", "workload": f"random block masks, B=1 H={H} N={N} d={d} bf16 non-causal, kernel only",
             "unit": "TOPS (4*N^2*d*H / kernel time)", "rows": rows}
 
@@ -273,7 +278,7 @@ def main():
     ap.add_argument("--no-also", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-detail", action="store_true")
-    ap.add_argument("--no-fp8", action="store_true", help="skip the FP8 P~V variant of each workload")
+    ap.add_argument("--no-fp8", action="store_true", help="skip the FP8 P~V and 16-bit Q K^T variants of each workload")
     ap.add_argument("--heads", type=int, default=0, help="debug: fewer heads (result is then not the headline)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy, the known-size dispatch that HBM counter "
@@ -301,7 +306,7 @@ def main():
         del src, dst
     names = [args.workload] + ([] if args.no_also else [n for n in args.also.split(",") if n and n != args.workload])
     workers = min(16, os.cpu_count() or 1)
-    results, fp8_results, cpu = {}, {}, None
+    results, fp8_results, qk16_results, cpu = {}, {}, {}, None
     for name in names:
         w = CONFIGS[name]
         if args.heads:
@@ -325,6 +330,12 @@ def main():
             log(f"  {name}, FP8 P~V: {r8['ms_per_step']:.3f} ms/step, {r8['tops']:.1f} dense-equivalent TOPS, "
                 f"attn kernel {r8['attn_kernel_ms']:.3f} ms, MFMA frac {r8['roofline']['frac']:.3f}")
             fp8_results[name] = r8
+            if w.N <= 65536:
+                # and with the Q K^T product on the 16-bit tensors themselves (the paper's "+FA2" variant)
+                r16, _ = run_workload(w, data, args.steps, args.warmup, detail=False, qk16=True)
+                log(f"  {name}, 16-bit Q K^T: {r16['ms_per_step']:.3f} ms/step, {r16['tops']:.1f} dense-equivalent TOPS, "
+                    f"attn kernel {r16['attn_kernel_ms']:.3f} ms, MFMA frac {r16['roofline']['frac']:.3f}")
+                qk16_results[name] = r16
         del data
 
     w, res = results[args.workload]
@@ -356,6 +367,12 @@ def main():
             name: {"dtype": "int8 QK^T + fp8 e4m3 P~V (fp32 softmax)", "value": r["tops"], "unit": "TOPS",
                    "ms_per_step": r["ms_per_step"], "sparsity": r["sparsity"], "attn_kernel_ms": r["attn_kernel_ms"],
                    "roofline": r["roofline"]} for name, r in fp8_results.items()}
+    if qk16_results:
+        line["unquantized_qk_variant"] = {
+            name: {"dtype": "%s QK^T + %s P~V (fp32 softmax)" % (CONFIGS[name].dtype, CONFIGS[name].dtype),
+                   "value": r["tops"], "unit": "TOPS", "ms_per_step": r["ms_per_step"], "sparsity": r["sparsity"],
+                   "attn_kernel_ms": r["attn_kernel_ms"], "roofline": r["roofline"]}
+            for name, r in qk16_results.items()}
     print(json.dumps(line))
 
 

@@ -42,6 +42,12 @@ enum { SPARGE_MAX_HEADS = 128, SPARGE_MAX_TN = 4096 };
 enum { SPARGE_REF_SLACK_LOG2 = 8, SPARGE_REF_SLACK_LOG2_FP8 = 2 };
 /* sparge_desc.pv_dtype: type of the P~V product (Alg. 1 line 16) */
 enum { SPARGE_PV_16BIT = 0 /* the tensors' fp16/bf16 */, SPARGE_PV_FP8 = 1 /* OCP E4M3, see sparge_v_tiles */ };
+/* sparge_desc.qk_dtype: type of the Q K^T product (Alg. 1 line 12).  SPARGE_QK_16BIT is the paper's
+ * "SpargeAttn+FA2" variant (Sec. 4.3): the same two-stage filter on an unquantized kernel -- Q and K
+ * enter the product as they are (no K smoothing is needed: it does not change the softmax), scores
+ * accumulate in fp32, S = Q_i K_j^T * sm_scale.  Read by sparge_attn and sparge_forward only; not built
+ * together with SPARGE_PV_FP8, for N <= 65536. */
+enum { SPARGE_QK_INT8 = 0, SPARGE_QK_16BIT = 1 };
 
 /* which entry point a workspace is sized for */
 enum { SPARGE_WS_QUANTIZE = 0, SPARGE_WS_PREDICT = 1, SPARGE_WS_ATTN = 2, SPARGE_WS_ATTN_QUANTIZED = 3,
@@ -52,6 +58,7 @@ typedef struct sparge_desc {
     int32_t dtype;                          /* SPARGE_F16 | SPARGE_BF16 */
     int64_t stride_b, stride_h, stride_n;   /* in elements; the d axis is contiguous */
     int32_t pv_dtype;                       /* SPARGE_PV_16BIT | SPARGE_PV_FP8; only the attention entry points read it */
+    int32_t qk_dtype;                       /* SPARGE_QK_INT8 | SPARGE_QK_16BIT */
 } sparge_desc;
 
 /* Description of the last error on the calling thread (host string, never NULL). */

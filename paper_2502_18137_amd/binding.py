@@ -28,7 +28,7 @@ class SpargeError(RuntimeError):
 class _Desc(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int32), ("d", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64),
-                ("stride_n", ctypes.c_int64), ("pv_dtype", ctypes.c_int32)]
+                ("stride_n", ctypes.c_int64), ("pv_dtype", ctypes.c_int32), ("qk_dtype", ctypes.c_int32)]
 
 
 def library_path() -> str:
@@ -89,7 +89,7 @@ def _check(rc: int) -> None:
         raise SpargeError(f"libsparge error {rc}: {load_library().sparge_last_error().decode()}")
 
 
-def _desc(x: torch.Tensor, pv_fp8: bool = False) -> _Desc:
+def _desc(x: torch.Tensor, pv_fp8: bool = False, qk16: bool = False) -> _Desc:
     if x.dim() != 4:
         raise SpargeError("expected a [B, H, N, d] tensor")
     if not x.is_cuda:
@@ -103,7 +103,7 @@ def _desc(x: torch.Tensor, pv_fp8: bool = False) -> _Desc:
     else:
         raise SpargeError(f"dtype {x.dtype} not supported (fp16 or bf16)")
     B, H, N, d = x.shape
-    return _Desc(B, H, N, d, dt, x.stride(0), x.stride(1), x.stride(2), 1 if pv_fp8 else 0)
+    return _Desc(B, H, N, d, dt, x.stride(0), x.stride(1), x.stride(2), 1 if pv_fp8 else 0, 1 if qk16 else 0)
 
 
 def _same_layout(ref: torch.Tensor, *others: torch.Tensor) -> None:
@@ -257,10 +257,11 @@ def sparge_attn_tiled(Qq, Kq, q_scale, k_scale, v_tiles: torch.Tensor, like: tor
 
 def sparge_attn(Q, K, V, mask: Optional[torch.Tensor], lam, causal: bool = False, sm_scale: float = 0.0,
                 return_stats: bool = False, ws: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
-                pv_fp8: bool = False):
-    """Quantize + sparse attention.  -> O (and stats)."""
+                pv_fp8: bool = False, qk16: bool = False):
+    """Quantize + sparse attention.  -> O (and stats).  qk16: the Q K^T product on the 16-bit tensors
+    themselves instead of their INT8 quantization."""
     _same_layout(Q, K, V)
-    d = _desc(Q, pv_fp8)
+    d = _desc(Q, pv_fp8, qk16)
     B, H, N, _ = Q.shape
     Tm, Tn = _blocks(N)
     if mask is not None and (tuple(mask.shape) != (B, H, Tm, Tn) or mask.dtype != torch.uint8
@@ -278,10 +279,10 @@ def sparge_attn(Q, K, V, mask: Optional[torch.Tensor], lam, causal: bool = False
 
 def sparge_forward(Q, K, V, tau, theta, lam, causal: bool = False, sm_scale: float = 0.0,
                    return_mask: bool = False, return_stats: bool = False, ws: Optional[torch.Tensor] = None,
-                   out: Optional[torch.Tensor] = None, pv_fp8: bool = False):
+                   out: Optional[torch.Tensor] = None, pv_fp8: bool = False, qk16: bool = False):
     """All of Algorithm 1.  -> O (and mask, stats when requested, in that order)."""
     _same_layout(Q, K, V)
-    d = _desc(Q, pv_fp8)
+    d = _desc(Q, pv_fp8, qk16)
     B, H, N, _ = Q.shape
     Tm, Tn = _blocks(N)
     O = torch.empty_like(V) if out is None else out

@@ -49,6 +49,13 @@ int check_desc(const sparge_desc* d, Shape* s) {
     if (d->pv_dtype != SPARGE_PV_16BIT && d->pv_dtype != SPARGE_PV_FP8)
         return fail(SPARGE_EUNSUPPORTED, "pv_dtype %d not supported", d->pv_dtype);
     s->pv_fp8 = d->pv_dtype == SPARGE_PV_FP8;
+    if (d->qk_dtype != SPARGE_QK_INT8 && d->qk_dtype != SPARGE_QK_16BIT)
+        return fail(SPARGE_EUNSUPPORTED, "qk_dtype %d not supported", d->qk_dtype);
+    s->qk16 = d->qk_dtype == SPARGE_QK_16BIT;
+    if (s->qk16 && s->pv_fp8) return fail(SPARGE_EUNSUPPORTED, "the 16-bit Q K^T product is not built with the FP8 P~V product");
+    if (s->qk16 && Tn > 1024) return fail(SPARGE_EUNSUPPORTED, "the 16-bit Q K^T product takes at most 1024 key blocks (N <= 65536)");
+    if (s->qk16 && (double)Tn * BK * d->stride_n * 2.0 >= 4294967296.0)
+        return fail(SPARGE_EUNSUPPORTED, "the 16-bit Q K^T product needs a head's K to span less than 4 GiB");
     return SPARGE_OK;
 }
 
@@ -174,7 +181,7 @@ int run_predict(const Shape& s, void* ws, const Workspace& w, const HeadParams& 
 }
 
 // The attention launch, bracketed by the caller's timing events when some are installed.
-int timed_attn(const int8_t* Qq, const int8_t* Kq, const float* q_scale, const float* k_scale,
+int timed_attn(const void* Qq, const void* Kq, const float* q_scale, const float* k_scale,
                const void* v_tiles, const Shape& s, const uint8_t* mask, const HeadParams& lam, float sm_scale,
                int causal, void* O, uint64_t* stats, hipStream_t st) {
     const bool timed = g_ev_start && g_ev_k < g_ev_n;
@@ -194,7 +201,7 @@ int timed_attn(const int8_t* Qq, const int8_t* Kq, const float* q_scale, const f
     return SPARGE_OK;
 }
 
-int run_attn(const int8_t* Qq, const int8_t* Kq, const float* q_scale, const float* k_scale, const void* V,
+int run_attn(const void* Qq, const void* Kq, const float* q_scale, const float* k_scale, const void* V,
              const Shape& s, void* v_tiles, const uint8_t* mask, const HeadParams& lam, float sm_scale,
              int causal, void* O, uint64_t* stats, hipStream_t st) {
     hipError_t e;
@@ -327,6 +334,8 @@ int sparge_attn(const void* Q, const void* K, const void* V, const sparge_desc* 
     const Workspace w = plan(s, SPARGE_WS_ATTN);
     if ((rc = check_ws(w, ws, ws_bytes))) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (s.qk16)  // the products run on Q and K as they are: nothing to quantize
+        return run_attn(Q, K, nullptr, nullptr, V, s, at<char>(ws, w.v_tiles), mask, lam, sm_scale, causal, O, stats, st);
     if ((rc = run_stats_and_quant(Q, K, s, at<double>(ws, w.pooled_q), at<double>(ws, w.ksum_t),
                                   at<double>(ws, w.sim_q), at<double>(ws, w.sim_k), at<int8_t>(ws, w.Qq),
                                   at<float>(ws, w.q_scale), at<int8_t>(ws, w.Kq), at<float>(ws, w.k_scale),
@@ -350,12 +359,15 @@ int sparge_forward(const void* Q, const void* K, const void* V, const sparge_des
     const Workspace w = plan(s, SPARGE_WS_FORWARD);
     if ((rc = check_ws(w, ws, ws_bytes))) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const bool q8 = !s.qk16;  // the 16-bit product needs the block statistics only
     if ((rc = run_stats_and_quant(Q, K, s, at<double>(ws, w.pooled_q), at<double>(ws, w.ksum_t),
-                                  at<double>(ws, w.sim_q), at<double>(ws, w.sim_k), at<int8_t>(ws, w.Qq),
-                                  at<float>(ws, w.q_scale), at<int8_t>(ws, w.Kq), at<float>(ws, w.k_scale),
-                                  at<float>(ws, w.k_mean), st))) return rc;
+                                  at<double>(ws, w.sim_q), at<double>(ws, w.sim_k), q8 ? at<int8_t>(ws, w.Qq) : nullptr,
+                                  q8 ? at<float>(ws, w.q_scale) : nullptr, q8 ? at<int8_t>(ws, w.Kq) : nullptr,
+                                  at<float>(ws, w.k_scale), at<float>(ws, w.k_mean), st))) return rc;
     uint8_t* mask = mask_out ? mask_out : at<uint8_t>(ws, w.mask);
     if ((rc = run_predict(s, ws, w, t, th, sm_scale, causal, mask, st))) return rc;
+    if (s.qk16)
+        return run_attn(Q, K, nullptr, nullptr, V, s, at<char>(ws, w.v_tiles), mask, lam, sm_scale, causal, O, stats, st);
     return run_attn(at<int8_t>(ws, w.Qq), at<int8_t>(ws, w.Kq), at<float>(ws, w.q_scale), at<float>(ws, w.k_scale),
                     V, s, at<char>(ws, w.v_tiles), mask, lam, sm_scale, causal, O, stats, st);
 }

@@ -17,6 +17,7 @@ struct Shape {
     long long sb, sh, sn;  // element strides of the 16-bit tensors
     int Tm, Tn;
     int pv_fp8;            // P~V product in FP8 (E4M3) instead of the tensors' 16-bit type
+    int qk16;              // Q K^T product on the 16-bit tensors themselves instead of their INT8 quantization
 };
 
 // Per-head scalars travel to the device inside the kernel argument block.
@@ -80,7 +81,7 @@ hipError_t launch_v_tiles(const void* V, const Shape& s, uint16_t* v_tiles, hipS
 // stats[0..n) = 0 (a fill kernel, not a memset node, so callers may capture it in a graph).
 hipError_t launch_zero_stats(unsigned long long* stats, int n, hipStream_t st);
 // The sparse flash loop (accumulates into stats).
-hipError_t launch_attn(const int8_t* Qq, const int8_t* Kq, const float* q_scale, const float* k_scale,
+hipError_t launch_attn(const void* Qp, const void* Kp, const float* q_scale, const float* k_scale,
                        const void* v_tiles, const float* v_scale, const Shape& s, const uint8_t* mask,
                        const HeadParams& lambda, float sm_scale, int causal, void* O, unsigned long long* stats,
                        hipStream_t st);

@@ -49,15 +49,20 @@ NWAVE = 4               # waves per workgroup sharing the tile copies
 
 
 class Cfg:
-    def __init__(self, D, dt):
-        self.D, self.dt = D, dt
-        self.NSTEP = self.NDT = D // 32
+    def __init__(self, D, dt, qk16=False):
+        self.D, self.dt, self.qk16 = D, dt, qk16
+        # Q K^T: INT8 32x32x32 MFMAs on quantized operands, or (qk16) 32x32x16 MFMAs on the 16-bit tensors
+        # themselves: twice the steps along d, twice the bytes per K row, fp32 scores
+        self.NSTEP = D // 16 if qk16 else D // 32
+        self.NDT = D // 32
+        self.KROW = D * (2 if qk16 else 1)       # bytes of one K row in LDS
         self.fp8 = dt == "fp8"
+        assert not (self.fp8 and qk16)
         # P~V: 16-bit 32x32x16 MFMAs (4 key steps per channel tile) or one FP8 32x32x64 MFMA per channel tile
         self.NQK, self.NPV = 2 * self.NSTEP, (self.NDT if self.fp8 else 4 * self.NDT)
         self.NSLOT = self.NQK + self.NPV
         self.NUNIT = self.NQK + (2 * self.NDT if self.fp8 else self.NPV)   # 16-byte operand reads per step
-        self.K_BYTES, self.V_BYTES = 64 * D, (D * 64 if self.fp8 else D * 128)
+        self.K_BYTES, self.V_BYTES = 64 * self.KROW, (D * 64 if self.fp8 else D * 128)
         self.NP = 2 if self.fp8 else 4           # registers quads of one P~ tile
         # how far the row maximum may run ahead of the reference (log2 units); with FP8 P~ is scaled by
         # 448 / 2^T so that its largest possible value is the largest E4M3 number
@@ -67,7 +72,8 @@ class Cfg:
         # ---- VGPRs (pinned; the kernel uses no AGPRs, so all 256 registers of a wave are VGPRs) ----
         self.S = (0, 32)
         self.P = (64, 80)
-        self.MG, self.RG = 96, 112                # accumulator start value; ring of operand registers
+        # accumulator start value of the INT8 products (qk16 starts from the constant 0); ring of operand registers
+        self.MG, self.RG = (None, 96) if qk16 else (96, 112)
         nxt = self.RG + 4 * RING
         (self.MT, self.MR, self.L, self.INV, self.CX) = range(nxt, nxt + 5)
         nxt += 5
@@ -75,8 +81,8 @@ class Cfg:
         self.L0, self.L1, self.L2 = nxt, nxt + 1, nxt + 2  # list prefetch: read back before the temporaries are used
         self.MLOC = nxt + 2
         nxt += 3
-        self.KA, self.VA = nxt, nxt + 4           # per-lane LDS addresses of the operand reads in buffer 0
-        nxt += 8
+        self.KA, self.VA = nxt, nxt + self.NSTEP  # per-lane LDS addresses of the operand reads in buffer 0
+        nxt += self.NSTEP + 4
         self.KSRC = nxt                           # KD registers: global offsets of this wave's K_hat copy pieces
         self.VSRC = nxt + self.KD                 # VD registers: the same for V
         self.KSRCC = self.VSRC + self.VD          # KD registers: K_hat pieces of a partial last block (rows clamped)
@@ -91,7 +97,7 @@ class Cfg:
         assert self.NVGPR <= 256
         # ---- SGPRs (pinned) ----
         names = ("u jpart kb0 kb1 vb0 vb1 ldskd ldsvd ldsjl ldsscl lam2 exec pv scx scn jk jv negmagic rt scnn "
-                 "t0 t1 a0 a1 b0 b1 cnt ufull jn mlim ex0 ex1 exp0 exp1 hf0 hf1").split()
+                 "t0 t1 a0 a1 b0 b1 cnt ufull jn mlim ex0 ex1 exp0 exp1 hf0 hf1 ktile").split()
         self.sg = {n: 36 + i for i, n in enumerate(names)}
         for n in "kb0 vb0 a0 b0 ex0 exp0 hf0".split():
             assert self.sg[n] % 2 == 0, (n, self.sg)
@@ -127,7 +133,7 @@ def gen_step(c, o, cur, NST, kbuf, vbuf, masked, pv, dkbuf, dvbuf, label, late):
         dst = c.RG + 4 * (un % RING)
         if un < c.NQK:
             kh, st = un % 2, un // 2
-            o(f"ds_read_b128 {vr(dst, 4)}, v{c.KA + st} offset:{kbuf * c.K_BYTES + kh * 32 * c.D}")
+            o(f"ds_read_b128 {vr(dst, 4)}, v{c.KA + st} offset:{kbuf * c.K_BYTES + kh * 32 * c.KROW}")
         elif c.fp8:
             dt, h2 = divmod(un - c.NQK, 2)
             o(f"ds_read_b128 {vr(dst, 4)}, v{c.VA} offset:{vbuf * c.V_BYTES + dt * 2048 + h2 * 1024}")
@@ -141,8 +147,12 @@ def gen_step(c, o, cur, NST, kbuf, vbuf, masked, pv, dkbuf, dvbuf, label, late):
         if sl < c.NQK:
             kh, st = sl % 2, sl // 2
             d = YS + 16 * kh
-            acc = vr(c.MG, 16) if st == 0 else vr(d, 16)
-            o(f"v_mfma_i32_32x32x32_i8 {vr(d, 16)}, {vr(src, 4)}, {vr(c.Q + 4 * st, 4)}, {acc}")
+            if c.qk16:
+                acc = "0" if st == 0 else vr(d, 16)
+                o(f"v_mfma_f32_32x32x16_{c.dt} {vr(d, 16)}, {vr(src, 4)}, {vr(c.Q + 4 * st, 4)}, {acc}")
+            else:
+                acc = vr(c.MG, 16) if st == 0 else vr(d, 16)
+                o(f"v_mfma_i32_32x32x32_i8 {vr(d, 16)}, {vr(src, 4)}, {vr(c.Q + 4 * st, 4)}, {acc}")
         elif c.fp8:
             dt = sl - c.NQK
             a = c.O + 16 * dt
@@ -180,18 +190,21 @@ def gen_step(c, o, cur, NST, kbuf, vbuf, masked, pv, dkbuf, dvbuf, label, late):
             koff = (e >> 4) * 32 + 8 * ((e & 15) >> 2) + (e & 3)
             ops.append((f"v_cmp_le_i32 vcc, {koff}, v{T1}", 1))
             ops.append((f"v_cndmask_b32 v{y(e)}, v{T2}, v{y(e)}, vcc", 1))
-    # row maximum of the fresh scores (biased integers compare like the scores themselves)
+    # row maximum of the fresh scores (biased integers compare like the scores themselves; fp32 scores of
+    # the 16-bit product can be negative and take the float comparison)
+    mx = "f32" if c.qk16 else "i32"
     chains = []
     for t, base in ((T0, y(0)), (T1, y(16))):
-        ch = [f"v_max3_i32 v{t}, v{base}, v{base + 1}, v{base + 2}"]
-        ch += [f"v_max3_i32 v{t}, v{t}, v{base + i}, v{base + i + 1}" for i in range(3, 15, 2)]
-        ch += [f"v_max_i32 v{t}, v{t}, v{base + 15}"]
+        ch = [f"v_max3_{mx} v{t}, v{base}, v{base + 1}, v{base + 2}"]
+        ch += [f"v_max3_{mx} v{t}, v{t}, v{base + i}, v{base + i + 1}" for i in range(3, 15, 2)]
+        ch += [f"v_max_{mx} v{t}, v{t}, v{base + 15}"]
         chains.append(ch)
     for a_, b_ in zip(*chains):
         ops.append((a_, 1)); ops.append((b_, 1))
-    tail = [f"v_max_i32 v{T0}, v{T0}, v{T1}",
-            f"v_add_f32 v{T0}, s{s['negmagic']}, v{T0}",      # biased integer (as float) -> integer score
-            f"v_mul_f32 v{T0}, s{s['scn']}, v{T0}",           # -> log2-domain score
+    tail = [f"v_max_{mx} v{T0}, v{T0}, v{T1}"]
+    if not c.qk16:
+        tail += [f"v_add_f32 v{T0}, s{s['negmagic']}, v{T0}"]  # biased integer (as float) -> integer score
+    tail += [f"v_mul_f32 v{T0}, s{s['scn']}, v{T0}",           # -> log2-domain score
             f"v_mov_b32 v{T1}, v{T0}",
             "s_nop 1",
             f"v_permlane32_swap_b32 v{T0}, v{T1}",            # exchange with the lane holding the other 16 keys
@@ -202,6 +215,7 @@ def gen_step(c, o, cur, NST, kbuf, vbuf, masked, pv, dkbuf, dvbuf, label, late):
             f"v_sub_f32 v{T1}, v{c.MT}, v{c.MR}",
             f"v_add_f32 v{T0}, v{T0}, v{c.INV}",              # rows past N: -inf
             f"v_add_f32 v{T1}, v{T1}, v{c.INV}"]
+    assert all(isinstance(t, str) for t in tail)
 
     # chunk 0 runs before the first MFMA, chunk sl + 1 after MFMA sl
     if pv:
@@ -289,7 +303,7 @@ def gen_step(c, o, cur, NST, kbuf, vbuf, masked, pv, dkbuf, dvbuf, label, late):
             # this wave's pieces of K_hat(jk) and V(jv): group u+NST-1 = {K_hat(u+NST), V(u+NST-2)}.  The
             # lists are padded with their last entry, so the copies near the end of the list fetch a tile
             # nobody reads instead of being skipped, and every iteration issues the same number of loads.
-            o(f"s_mul_i32 s{s['t0']}, s{s['jk']}, {c.K_BYTES}")
+            o(f"s_mul_i32 s{s['t0']}, s{s['jk']}, s{s['ktile']}")   # bytes between K tiles in memory
             o(f"s_add_u32 s{s['a0']}, s{s['kb0']}, s{s['t0']}")
             o(f"s_addc_u32 s{s['a1']}, s{s['kb1']}, 0")
             o(f"s_mul_i32 s{s['t1']}, s{s['jv']}, {c.V_BYTES}")
@@ -375,7 +389,7 @@ def gen_loop(c, NST):
     lines = []
     o = lines.append
     period = 2 * NST if NST % 2 else NST  # bodies: one set per value of u mod lcm(2, NST)
-    o(f"s_mov_b32 s{s['negmagic']}, 0x{MAGIC_NEG:08x}")
+    o(f"s_mov_b32 s{s['negmagic']}, 0x{0 if c.qk16 else MAGIC_NEG:08x}")   # fp32 scores carry no bias
     o(f"s_mov_b32 s{s['rt']}, 0x{RESCALE_T[c.T_LOG2]:08x}")
     o(f"s_cmp_lg_u32 s{s['exec']}, 0")                 # stage-2 decision of tile 0 as a lane mask
     o(f"s_cselect_b64 {sp(s, 'ex0')}, -1, 0")
@@ -445,13 +459,14 @@ def gen_function(c, NST):
     s = c.sg
     body = gen_loop(c, NST)
     dtn = {"bf16": "SPARGE_BF16", "f16": "SPARGE_F16", "fp8": "PV_FP8"}[c.dt]
+    qkn = "true" if c.qk16 else "false"
     io_names = "u jk jv scn scx pv".split()                       # read and written by the block
-    in_names = "exec jpart cnt ufull ldskd ldsvd ldsjl ldsscl lam2".split()
+    in_names = "exec jpart cnt ufull ldskd ldsvd ldsjl ldsscl lam2 ktile".split()
     floats = {"scn", "scx", "lam2"}
     out = []
     w = out.append
-    w(f"// head dimension {c.D}, {c.dt}, {NST} LDS stages: {c.NVGPR} VGPRs pinned, no AGPRs")
-    w(f"template <> struct FastLoop<{c.D}, {dtn}, {NST}> {{")
+    w(f"// head dimension {c.D}, {c.dt}{', 16-bit Q K^T' if c.qk16 else ''}, {NST} LDS stages: {c.NVGPR} VGPRs pinned, no AGPRs")
+    w(f"template <> struct FastLoop<{c.D}, {dtn}, {NST}, {qkn}> {{")
     w("    template <class St>")
     w("    static __device__ __forceinline__ void run(St& w, const v16i& magic, FastLoopArgs& p) {")
     # scalar operands go through readfirstlane copies: the register allocator then knows they are uniform
@@ -478,7 +493,8 @@ def gen_function(c, NST):
         outs.append(f'"+{{s{s[n]}}}"({n}_)')
     for st in range(c.NSTEP):
         ins.append(f'"{{{vr(c.Q + 4 * st, 4)}}}"(w.qf[{st}])')
-    ins.append(f'"{{{vr(c.MG, 16)}}}"(magic)')
+    if not c.qk16:
+        ins.append(f'"{{{vr(c.MG, 16)}}}"(magic)')
     ins.append(f'"{{v{c.INV}}}"(p.inval)')
     ins.append(f'"{{v{c.ROWLIM}}}"(p.rowlim)')
     for st in range(c.NSTEP):
@@ -513,6 +529,9 @@ def main():
         for dt in ("f16", "bf16", "fp8"):
             for NST in (2, 3):
                 out += gen_function(Cfg(D, dt), NST)
+        for dt in ("f16", "bf16"):
+            for NST in (2, 3):
+                out += gen_function(Cfg(D, dt, qk16=True), NST)
     with open(os.path.join(here, "attn_loop_gfx950.inc"), "w") as f:
         f.write("\n".join(out))
     print(f"wrote attn_loop_gfx950.inc ({len(out)} lines)")
