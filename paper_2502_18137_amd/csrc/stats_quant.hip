@@ -67,6 +67,8 @@ __global__ __launch_bounds__(256) void block_stats_kernel(const uint16_t* __rest
     __shared__ double lds_hat[4][D];
     __shared__ float lds_amax[4];
     __shared__ double lds_sq[4];
+    __shared__ double lds_inv[4][NL * RPW];
+    static_assert(NL * RPW <= 64, "a wave's rows must fit one lane each");
 
     uint4 raw[NL];
 #pragma unroll
@@ -80,6 +82,7 @@ __global__ __launch_bounds__(256) void block_stats_kernel(const uint16_t* __rest
 #pragma unroll
     for (int e = 0; e < 8; ++e) sraw[e] = shat[e] = 0.0;
     float amax = 0.f;
+    // squared norm of every row of this wave (NL * RPW of them), one value per row in LDS
 #pragma unroll
     for (int n = 0; n < NL; ++n) {
         float f[8];
@@ -93,7 +96,23 @@ __global__ __launch_bounds__(256) void block_stats_kernel(const uint16_t* __rest
         }
 #pragma unroll
         for (int m = 1; m < LPR; m <<= 1) nsq += shfl_xor_f64(nsq, m);
-        const double inv = nsq > 0.0 ? 1.0 / sqrt(nsq) : 0.0;
+        if (cchunk == 0) lds_inv[wave][n * RPW + rsub] = nsq;
+    }
+    // 1 / |row|: the fp64 square root and division are the expensive part, so each row's is evaluated by
+    // one lane only (a wave owns at most 64 rows) and handed to the lanes of that row through LDS
+    // (the exchange stays inside a wave, whose LDS accesses complete in program order: the wave barriers
+    // only keep the compiler from moving accesses across the hand-over points)
+    __builtin_amdgcn_wave_barrier();
+    if (lane < NL * RPW) {
+        const double nsq = lds_inv[wave][lane];
+        lds_inv[wave][lane] = nsq > 0.0 ? 1.0 / sqrt(nsq) : 0.0;
+    }
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int n = 0; n < NL; ++n) {
+        float f[8];
+        unpack8<DT>(raw[n], f);
+        const double inv = lds_inv[wave][n * RPW + rsub];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const double x = static_cast<double>(f[e]);
