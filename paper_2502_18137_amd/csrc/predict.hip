@@ -76,9 +76,9 @@ __global__ __launch_bounds__(256) void topcdf_kernel(const double* __restrict__ 
                                                       HeadParams tau_h, HeadParams theta_h, int causal,
                                                       int npad, uint8_t* __restrict__ mask) {
     extern __shared__ __align__(16) unsigned char smem[];
-    double* keys = reinterpret_cast<double*>(smem);                      // [npad]
-    uint16_t* idx = reinterpret_cast<uint16_t*>(keys + npad);            // [npad]
-    uint8_t* flag = reinterpret_cast<uint8_t*>(idx + npad);              // [npad]
+    double* keys = reinterpret_cast<double*>(smem);                      // [npad] probabilities by key block
+    unsigned long long* skey = reinterpret_cast<unsigned long long*>(keys + npad);  // [npad] sort keys
+    uint8_t* flag = reinterpret_cast<uint8_t*>(skey + npad);             // [npad]
     __shared__ double scratch[4];
     __shared__ double wave_tot[4];
 
@@ -121,27 +121,56 @@ __global__ __launch_bounds__(256) void topcdf_kernel(const double* __restrict__ 
             tot += p;
         }
         keys[j] = p;
-        idx[j] = static_cast<uint16_t>(j);
+        // Sort key: the probability's bit pattern (non-negative doubles order like integers) with its low
+        // 16 mantissa bits replaced by 0xFFFF - j: one 64-bit comparison ranks by (value descending, index
+        // ascending).  Values closer than 2^-36 relative may swap ranks; that moves a prefix mass by less
+        // than 2^-36, far inside the band in which a decision counts as a tie.
+        skey[j] = p < 0.0 ? 0ull
+                          : ((static_cast<unsigned long long>(__double_as_longlong(p)) & ~0xFFFFull) |
+                             static_cast<unsigned long long>(0xFFFF - j));
         flag[j] = 0;
     }
     tot = block_reduce(tot, false, scratch);  // also orders the LDS writes before the sort
 
-    // 3. bitonic sort: rank order = (value descending, index ascending)
-    for (int k = 2; k <= npad; k <<= 1) {
-        for (int jj = k >> 1; jj > 0; jj >>= 1) {
-            for (int t = tid; t < (npad >> 1); t += 256) {
-                const int lo = 2 * jj * (t / jj) + (t % jj);
-                const int hi = lo + jj;
-                const double ka = keys[lo], kb = keys[hi];
-                const uint16_t ia = idx[lo], ib = idx[hi];
-                const bool a_first = (ka > kb) || (ka == kb && ia < ib);
-                const bool want_a_first = (lo & k) == 0;
-                if (a_first != want_a_first) {
-                    keys[lo] = kb; keys[hi] = ka;
-                    idx[lo] = ib; idx[hi] = ia;
+    // 3. bitonic sort: rank order = (value descending, index ascending).  Each wave owns a quarter of the
+    // array: every compare-exchange at a distance inside a quarter touches the wave's own elements only,
+    // and a wave's LDS accesses complete in program order, so those stages need no workgroup barrier
+    // (the wave barrier only pins the compiler's order).  Only the few stages that reach across quarters
+    // are bracketed by barriers.
+    auto exchange = [&](int lo, int jj, int k) {
+        const int hi = lo + jj;
+        const unsigned long long ka = skey[lo], kb = skey[hi];
+        const bool a_first = ka > kb;   // keys are distinct except among the padding
+        const bool want_a_first = (lo & k) == 0;
+        if (a_first != want_a_first && ka != kb) {
+            skey[lo] = kb;
+            skey[hi] = ka;
+        }
+    };
+    const int epw = npad >> 2;  // elements per wave
+    if (epw >= 128) {
+        const int lane_ = tid & 63, seg = (tid >> 6) * epw;
+        for (int k = 2; k <= npad; k <<= 1) {
+            int jj = k >> 1;
+            if (jj >= epw) {
+                __syncthreads();
+                for (; jj >= epw; jj >>= 1) {
+                    for (int t = tid; t < (npad >> 1); t += 256) exchange(2 * jj * (t / jj) + (t % jj), jj, k);
+                    __syncthreads();
                 }
             }
-            __syncthreads();
+            for (; jj > 0; jj >>= 1) {
+                for (int t = lane_; t < (epw >> 1); t += 64) exchange(seg + 2 * jj * (t / jj) + (t % jj), jj, k);
+                __builtin_amdgcn_wave_barrier();
+            }
+        }
+        __syncthreads();
+    } else {
+        for (int k = 2; k <= npad; k <<= 1) {
+            for (int jj = k >> 1; jj > 0; jj >>= 1) {
+                for (int t = tid; t < (npad >> 1); t += 256) exchange(2 * jj * (t / jj) + (t % jj), jj, k);
+                __syncthreads();
+            }
         }
     }
 
@@ -149,7 +178,9 @@ __global__ __launch_bounds__(256) void topcdf_kernel(const double* __restrict__ 
     const int per = (npad + 255) / 256;  // consecutive ranks per thread
     const int r0 = tid * per;
     double local = 0.0;
-    for (int r = r0; r < min(r0 + per, npad); ++r) local += fmax(keys[r], 0.0);
+    auto rank_index = [&](int r) { return 0xFFFF - static_cast<int>(skey[r] & 0xFFFFull); };
+    auto rank_value = [&](int r) { return skey[r] ? keys[rank_index(r)] : 0.0; };   // padding ranks last, mass 0
+    for (int r = r0; r < min(r0 + per, npad); ++r) local += rank_value(r);
     // inclusive scan of `local` over the 256 threads
     const int lane = tid & 63, wave = tid >> 6;
     double incl = local;
@@ -164,9 +195,9 @@ __global__ __launch_bounds__(256) void topcdf_kernel(const double* __restrict__ 
     for (int w = 0; w < wave; ++w) before += wave_tot[w];
     const double thresh = tau * tot;
     for (int r = r0; r < min(r0 + per, npad); ++r) {
-        const double p = keys[r];
-        if (p > 0.0 && before < thresh) flag[idx[r]] = 1;
-        before += fmax(p, 0.0);
+        const double p = rank_value(r);
+        if (p > 0.0 && before < thresh) flag[rank_index(r)] = 1;
+        before += p;
     }
     __syncthreads();
 
@@ -201,7 +232,7 @@ hipError_t launch_topcdf(const double* logits, const double* sim_q, const double
                          hipStream_t st) {
     int npad = 2;
     while (npad < s.Tn) npad <<= 1;
-    const size_t smem = static_cast<size_t>(npad) * (sizeof(double) + sizeof(uint16_t) + 1);
+    const size_t smem = static_cast<size_t>(npad) * (sizeof(double) + sizeof(unsigned long long) + 1);
     dim3 grid(s.Tm, s.H, s.B);
     hipLaunchKernelGGL(topcdf_kernel, grid, dim3(256), smem, st, logits, sim_q, sim_k, s, tau, theta, causal,
                        npad, mask);
