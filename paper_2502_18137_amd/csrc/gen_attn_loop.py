@@ -297,7 +297,11 @@ def gen_step(c, o, cur, NST, kbuf, vbuf, masked, pv, dkbuf, dvbuf, label, late):
             for t in range(un + LA, issued):
                 read(t)
             o(f"s_waitcnt lgkmcnt({issued - (un + 2)})")
+        if sl == 0:   # while its MFMAs are being issued the wave goes first at the SIMD's arbiter; the other
+            o("s_setprio 2")   # wave of the SIMD fills in from its MFMA-free stretch (measured: +3 % at d = 64)
         mfma(sl)
+        if sl == NSLOT - 1:
+            o("s_setprio 0")
         ch = list(chunks[sl + 1])
         if sl == 0:
             # this wave's pieces of K_hat(jk) and V(jv): group u+NST-1 = {K_hat(u+NST), V(u+NST-2)}.  The
