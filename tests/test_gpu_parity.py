@@ -220,3 +220,19 @@ def test_image_config_two_heads(sp):
         assert not ((m_gpu[0, h] != pr.mask) & ~pr.dont_care).any()
         masks.append(pr.mask)
     check_attention(sp, w, x, Q, K, V, np.stack(masks)[None], w.lam)
+
+
+@pytest.mark.parametrize("variant", [{}, {"pv_fp8": True}, {"qk16": True}], ids=["int8_16bit", "fp8_pv", "qk16"])
+def test_batch_of_two_equals_two_single_calls(sp, variant):
+    """B = 2 (a batch stride next to the head stride): every (batch, head) is an independent problem, so the
+    batched call must reproduce the two single calls bit for bit, mask, counters and all."""
+    import torch
+    wa = small_workload("batch_a", N=900, d=128, dtype="bf16", H=2, seed=14)
+    wb = small_workload("batch_b", N=900, d=128, dtype="bf16", H=2, seed=15)
+    _, Qa, Ka, Va = gpu_inputs(wa)
+    _, Qb, Kb, Vb = gpu_inputs(wb)
+    Q, K, V = (torch.cat(p, dim=0) for p in ((Qa, Qb), (Ka, Kb), (Va, Vb)))
+    O, mask, stats = sp.sparge_forward(Q, K, V, wa.tau, wa.theta, wa.lam, return_mask=True, return_stats=True, **variant)
+    for b, (q, k, v) in enumerate(((Qa, Ka, Va), (Qb, Kb, Vb))):
+        o1, m1, s1 = sp.sparge_forward(q, k, v, wa.tau, wa.theta, wa.lam, return_mask=True, return_stats=True, **variant)
+        assert torch.equal(O[b:b + 1], o1) and torch.equal(mask[b:b + 1], m1) and torch.equal(stats[b:b + 1], s1)
