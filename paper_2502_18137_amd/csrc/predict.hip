@@ -23,33 +23,44 @@ __device__ __forceinline__ double shfl_up_f64(double v, int delta) {
     return __hiloint2double(hi, lo);
 }
 
-// Thread j owns key block j; RI pooled query rows are swept per workgroup so that the transposed
-// key sums ([d][Tn], lane-coalesced) are read once per RI rows.
-template <int D, int RI>
+// Compressed logits as an fp64 matrix product on the matrix cores: a wave computes 16 pooled query rows x 64
+// key blocks with v_mfma_f64_16x16x4_f64 (operands: lane = row or column + 16 * k; result register r of a
+// lane = row 4 r + lane / 16, column lane % 16).  The pooled queries are row-major, the key sums
+// transposed ([d][Tn]), so the B operand loads are lane-coalesced; both operands stay L2-resident.
+typedef double v4d __attribute__((ext_vector_type(4)));
+template <int D>
 __global__ __launch_bounds__(256) void logits_kernel(const double* __restrict__ pooled_q,
                                                       const double* __restrict__ ksum_t, Shape s,
                                                       double sm_scale, double* __restrict__ logits) {
     const long long bh = blockIdx.z;
-    const int i0 = blockIdx.y * RI;
-    const int j = blockIdx.x * 256 + threadIdx.x;
-    if (j >= s.Tn) return;
-    const double* kt = ksum_t + bh * D * s.Tn + j;
-    const double* q = pooled_q + (bh * s.Tm) * D;
-    double acc[RI];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i0 = (blockIdx.y * 4 + wave) * 16, j0 = blockIdx.x * 64;
+    if (i0 >= s.Tm) return;
+    const int l16 = lane & 15, kk = lane >> 4;
+    const double* qrow = pooled_q + (bh * s.Tm + min(i0 + l16, s.Tm - 1)) * D + kk;   // rows past Tm: a valid row, not stored
+    const double* kcol[4];
 #pragma unroll
-    for (int r = 0; r < RI; ++r) acc[r] = 0.0;
-    for (int c = 0; c < D; ++c) {
-        const double kv = kt[(long long)c * s.Tn];
+    for (int t = 0; t < 4; ++t) kcol[t] = ksum_t + bh * D * s.Tn + (long long)kk * s.Tn + min(j0 + 16 * t + l16, s.Tn - 1);
+    v4d acc[4];
 #pragma unroll
-        for (int r = 0; r < RI; ++r) {
-            const int rr = min(i0 + r, s.Tm - 1);  // uniform: scalar loads
-            acc[r] += q[(long long)rr * D + c] * kv;
-        }
+    for (int t = 0; t < 4; ++t) acc[t] = v4d{0.0, 0.0, 0.0, 0.0};
+#pragma unroll 4
+    for (int c = 0; c < D; c += 4) {
+        const double a = qrow[c];
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, kcol[t][(long long)c * s.Tn], acc[t], 0, 0, 0);
     }
-    const double cnt = static_cast<double>(min(BK, s.N - j * BK));
 #pragma unroll
-    for (int r = 0; r < RI; ++r) {
-        if (i0 + r < s.Tm) logits[(bh * s.Tm + i0 + r) * s.Tn + j] = sm_scale * (acc[r] / cnt);
+    for (int t = 0; t < 4; ++t) {
+        const int j = j0 + 16 * t + l16;
+        if (j >= s.Tn) continue;
+        const double cnt = static_cast<double>(min(BK, s.N - j * BK));
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int i = i0 + 4 * r + kk;
+            if (i < s.Tm) logits[(bh * s.Tm + i) * s.Tn + j] = sm_scale * (acc[t][r] / cnt);
+        }
     }
 }
 
@@ -219,11 +230,10 @@ __global__ __launch_bounds__(256) void topcdf_kernel(const double* __restrict__ 
 
 hipError_t launch_logits(const double* pooled_q, const double* ksum_t, const Shape& s, float sm_scale,
                          double* logits, hipStream_t st) {
-    constexpr int RI = 16;
-    dim3 grid((s.Tn + 255) / 256, (s.Tm + RI - 1) / RI, s.B * s.H);
+    dim3 grid((s.Tn + 63) / 64, (s.Tm + 63) / 64, s.B * s.H);
     const double scale = sm_scale > 0.f ? static_cast<double>(sm_scale) : 1.0 / sqrt(static_cast<double>(s.d));
-    if (s.d == 64) hipLaunchKernelGGL((logits_kernel<64, RI>), grid, dim3(256), 0, st, pooled_q, ksum_t, s, scale, logits);
-    else hipLaunchKernelGGL((logits_kernel<128, RI>), grid, dim3(256), 0, st, pooled_q, ksum_t, s, scale, logits);
+    if (s.d == 64) hipLaunchKernelGGL((logits_kernel<64>), grid, dim3(256), 0, st, pooled_q, ksum_t, s, scale, logits);
+    else hipLaunchKernelGGL((logits_kernel<128>), grid, dim3(256), 0, st, pooled_q, ksum_t, s, scale, logits);
     return hipGetLastError();
 }
 
