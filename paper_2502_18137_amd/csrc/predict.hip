@@ -102,6 +102,13 @@ __global__ __launch_bounds__(256) void topcdf_kernel(const double* __restrict__ 
     const double* sk = sim_k + bh * s.Tn;
     const double NEG = -__builtin_inf();
 
+    // A query block that is not self-similar keeps every (visible) key block: nothing to rank.
+    if (sim_q[bh * s.Tm + i] < theta) {
+        uint8_t* out_row = mask + (bh * s.Tm + i) * s.Tn;
+        for (int j = tid; j < s.Tn; j += 256) out_row[j] = (causal && j * BK > i * BQ + (BQ - 1)) ? 0 : 1;
+        return;
+    }
+
     // 1. masked logits and their maximum
     double mx = NEG;
     for (int j = tid; j < npad; j += 256) {
