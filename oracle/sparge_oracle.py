@@ -34,6 +34,13 @@ Readings of the paper where it is silent or ambiguous (each also listed in the d
     maximum itself at every tile (the recurrence exactly as printed); ref_slack > 0 lets it lag:
     before a tile's softmax, if some row of a 32-row group has m - m_ref > ref_slack, the whole
     group's reference moves to the running maximum.  Only the rounding of P~ can tell the difference.
+  * Which P~ the row sum sees (Alg. 1 writes the same symbol in lines 13 and 16 and never rounds):
+    l_rounded = False sums P~ before it is rounded for the product (the default, used by every pin);
+    l_rounded = True sums the rounded values, i.e. the very P~ that multiplies V, so that every output
+    row is an exact convex combination of rows of V up to the product's own rounding.  The two differ
+    by the rounding error of l, about 2^-9 / sqrt(#keys that matter) relative for bf16.  The GPU kernels
+    follow the default (a dot-instruction row sum over the packed P~ was measured slower on gfx950: it
+    shares the matrix pipe).
   * FP8 P~V (the paper only credits a SageAttention2-based kernel with it, footnote of Sec. 1; no
     formulas): pv_dtype = "fp8e4m3".  V is quantized per (head, channel) over all tokens to OCP E4M3
     (1-4-3 bits, bias 7, subnormals, largest finite value 448, round to nearest even):
@@ -346,7 +353,8 @@ class AttnResult:
 def sparse_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, mask: Optional[np.ndarray],
                      lam: float = -np.inf, scale: Optional[float] = None, causal: bool = False,
                      quant: bool = True, pv_dtype: str = "none",
-                     q_blocks: Optional[Sequence[int]] = None, ref_slack: float = 0.0) -> AttnResult:
+                     q_blocks: Optional[Sequence[int]] = None, ref_slack: float = 0.0,
+                     l_rounded: bool = False) -> AttnResult:
     """Algorithm 1's loop for one head.
 
     q_blocks: only these Q block indices i are processed (their rows of O and their share of the
@@ -359,6 +367,7 @@ def sparse_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, mask: Optional
     uses the unrounded P~.  mask=None means all ones.
     ref_slack (natural-log units): how far the running maximum may run ahead of the reference that
     exp subtracts (see the module header); 0 = the recurrence of Alg. 1 lines 12-16 as printed.
+    l_rounded: the row sum takes P~ after its rounding for the product (see the module header).
     """
     Q = np.asarray(Q, dtype=np.float64)
     K = np.asarray(K, dtype=np.float64)
@@ -425,8 +434,8 @@ def sparse_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, mask: Optional
             live = m_ref > NEG_INF
             m_safe = np.where(live, m_ref, 0.0)
             P = np.exp(S - m_safe[:, None])          # exp(-inf) = 0 for masked entries
-            l = l + P.sum(axis=1)
             Pr = round_e4m3(P * c_P) if fp8 else round16(P, pv_dtype)
+            l = l + ((Pr / c_P if fp8 else Pr) if l_rounded else P).sum(axis=1)
             for g0 in range(0, nr, ROW_GROUP):
                 g1 = min(g0 + ROW_GROUP, nr)
                 with np.errstate(invalid="ignore"):
@@ -487,10 +496,12 @@ def rel_l1(O: np.ndarray, O_ref: np.ndarray) -> float:
 
 def spargeattn(Q: np.ndarray, K: np.ndarray, V: np.ndarray, tau: float, theta: float, lam: float,
                causal: bool = False, scale: Optional[float] = None, quant: bool = True,
-               pv_dtype: str = "none", ref_slack: float = 0.0) -> Tuple[AttnResult, Prediction]:
+               pv_dtype: str = "none", ref_slack: float = 0.0,
+               l_rounded: bool = False) -> Tuple[AttnResult, Prediction]:
     """The whole of Algorithm 1 for one head: Quant, predict M_g, masked loop with the lambda skip."""
     pred = predict(Q, K, tau, theta, scale, causal)
-    res = sparse_attention(Q, K, V, pred.mask, lam, scale, causal, quant, pv_dtype, ref_slack=ref_slack)
+    res = sparse_attention(Q, K, V, pred.mask, lam, scale, causal, quant, pv_dtype, ref_slack=ref_slack,
+                           l_rounded=l_rounded)
     return res, pred
 
 
@@ -511,7 +522,7 @@ class TuneResult:
 def tune_head(inputs: Sequence[Tuple[np.ndarray, np.ndarray, np.ndarray]], tau_grid: Sequence[float],
               theta_grid: Sequence[float], lam_grid: Sequence[float], l1: float, l2: float,
               causal: bool = False, scale: Optional[float] = None, pv_dtype: str = "none",
-              ref_slack: float = 0.0) -> TuneResult:
+              ref_slack: float = 0.0, l_rounded: bool = False) -> TuneResult:
     """Sec. 3.6 for one attention head and a handful of inputs (Q, K, V).
 
     The error of a setting is L1 = sum|O - O'| / sum|O| with O the full attention computed the same way
@@ -528,13 +539,13 @@ def tune_head(inputs: Sequence[Tuple[np.ndarray, np.ndarray, np.ndarray]], tau_g
     def out(res):
         return round16(res.O, pv_dtype) if pv_dtype in ("fp16", "bf16") else res.O
 
-    refs = [out(sparse_attention(Q, K, V, None, -np.inf, scale, causal, True, pv_dtype, ref_slack=ref_slack))
-            for (Q, K, V) in inputs]
+    refs = [out(sparse_attention(Q, K, V, None, -np.inf, scale, causal, True, pv_dtype, ref_slack=ref_slack,
+                                 l_rounded=l_rounded)) for (Q, K, V) in inputs]
 
     def evaluate(tau, theta, lam):
         sp, err = [], []
         for (Q, K, V), ref in zip(inputs, refs):
-            res, _ = spargeattn(Q, K, V, tau, theta, lam, causal, scale, True, pv_dtype, ref_slack)
+            res, _ = spargeattn(Q, K, V, tau, theta, lam, causal, scale, True, pv_dtype, ref_slack, l_rounded)
             sp.append(res.sparsity)
             err.append(rel_l1(out(res), ref))
         return float(np.mean(sp)), float(np.max(err))

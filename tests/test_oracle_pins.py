@@ -762,3 +762,24 @@ def test_token_permutation_round_trip_and_attention_invariance():
     O = so.dense_attention(Q, K, V)
     Op = so.dense_attention(*(so.permute_tokens(T, perm, off) for T in (Q, K, V)))
     np.testing.assert_allclose(so.permute_tokens(Op, perm, off, inverse=True), O, rtol=0, atol=1e-12)
+
+
+def test_row_sum_over_the_rounded_p_gives_convex_combinations():
+    """l_rounded: the row sum takes the very P~ that multiplies V.  With V = 1 in every channel the output is
+    then exactly 1 (weights sum to one), where the default reading gives rowsum(round(P~)) / rowsum(P~);
+    the two readings differ by the rounding error of l only."""
+    Q, K, V = _peaky_inputs(46, N=384)
+    ones = np.ones_like(V)
+    for dt in ("bf16", "fp16"):
+        a = so.sparse_attention(Q, K, ones, None, quant=False, pv_dtype=dt, l_rounded=True).O
+        np.testing.assert_allclose(a, 1.0, rtol=0, atol=1e-13)
+        b = so.sparse_attention(Q, K, ones, None, quant=False, pv_dtype=dt).O
+        assert 0 < np.abs(b - 1.0).max() < 2.0 ** -8
+        x = so.sparse_attention(Q, K, V, None, quant=False, pv_dtype=dt, l_rounded=True).O
+        y = so.sparse_attention(Q, K, V, None, quant=False, pv_dtype=dt).O
+        ratio = y / x                                  # the same numerators over two row sums
+        assert np.abs(ratio - ratio[:, :1]).max() < 1e-12 and np.abs(ratio - 1.0).max() < 2.0 ** -8
+    # without rounding the option changes nothing
+    u = so.sparse_attention(Q, K, V, None, quant=False, pv_dtype="none", l_rounded=True).O
+    w = so.sparse_attention(Q, K, V, None, quant=False, pv_dtype="none").O
+    np.testing.assert_array_equal(u, w)
