@@ -39,6 +39,10 @@ def _hipcc() -> str:
 def build_library(verbose: bool = True) -> str:
     hipcc = _hipcc()
     os.makedirs(OBJ_DIR, exist_ok=True)
+    # the attention loop's assembly is generated: rewrite it so that it cannot lag behind its generator
+    r = subprocess.run([sys.executable, os.path.join(CSRC, "gen_attn_loop.py")], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"gen_attn_loop.py failed:\n{r.stdout}\n{r.stderr}")
 
     def compile_one(item):
         src, extra = item
