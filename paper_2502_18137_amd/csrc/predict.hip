@@ -233,6 +233,149 @@ __global__ __launch_bounds__(256) void topcdf_kernel(const double* __restrict__ 
     }
 }
 
+// TopCdf with one mask row per wave and the sort in registers: lane L holds the EPL consecutive ranks
+// L * EPL .. L * EPL + EPL - 1 as 64-bit keys (see topcdf_kernel for the key).  A bitonic stage at a distance
+// below EPL exchanges inside a lane (compile-time register indices), a larger one takes the partner
+// lane's key with a shuffle; nothing but the final flags and the exact probabilities goes through LDS,
+// and no workgroup barrier is needed.  Same comparisons, hence the same order, as the LDS version.
+template <int EPL>
+__global__ __launch_bounds__(256) void topcdf_wave_kernel(const double* __restrict__ logits,
+                                                           const double* __restrict__ sim_q,
+                                                           const double* __restrict__ sim_k, Shape s,
+                                                           HeadParams tau_h, HeadParams theta_h, int causal,
+                                                           int n_rows, uint8_t* __restrict__ mask) {
+    constexpr int NPAD = 64 * EPL;
+    __shared__ double pval[4][NPAD];
+    __shared__ uint8_t flag[4][NPAD];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int rowid = blockIdx.x * 4 + wave;          // (b, h, i) flattened
+    if (rowid >= n_rows) return;
+    const int i = rowid % s.Tm;
+    const long long bh = rowid / s.Tm;
+    const int h = static_cast<int>(bh % s.H);
+    const double tau = static_cast<double>(tau_h.v[h]);
+    const double theta = static_cast<double>(theta_h.v[h]);
+    const double* row = logits + (long long)rowid * s.Tn;
+    const double* sk = sim_k + bh * s.Tn;
+    uint8_t* out = mask + (long long)rowid * s.Tn;
+    const double NEG = -__builtin_inf();
+    if (sim_q[rowid] < theta) {   // a query block that is not self-similar keeps every visible key block
+        for (int j = lane; j < s.Tn; j += 64) out[j] = (causal && j * BK > i * BQ + (BQ - 1)) ? 0 : 1;
+        return;
+    }
+    auto wave_sum = [&](double v) {
+#pragma unroll
+        for (int m = 1; m < 64; m <<= 1) v += shfl_xor_f64(v, m);
+        return v;
+    };
+    // 1.-2. masked logits, softmax, probabilities (entries lane * EPL + e: a lane reads one contiguous piece)
+    double x[EPL];
+    double mx = NEG;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+        const int j = lane * EPL + e;
+        x[e] = NEG;
+        if (j < s.Tn) {
+            x[e] = row[j];
+            if (sk[j] < theta) x[e] = NEG;
+            if (causal && j * BK > i * BQ + (BQ - 1)) x[e] = NEG;
+        }
+        mx = fmax(mx, x[e]);
+    }
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) mx = fmax(mx, shfl_xor_f64(mx, m));
+    double z = 0.0;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+        x[e] = (x[e] == NEG) ? 0.0 : exp(x[e] - mx);
+        z += x[e];
+    }
+    z = wave_sum(z);
+    double tot = 0.0;
+    unsigned long long key[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+        const int j = lane * EPL + e;
+        const double p = (j < s.Tn && z > 0.0) ? x[e] / z : 0.0;
+        tot += p;
+        pval[wave][j] = p;
+        flag[wave][j] = 0;
+        key[e] = j < s.Tn ? ((static_cast<unsigned long long>(__double_as_longlong(p)) & ~0xFFFFull) |
+                             static_cast<unsigned long long>(0xFFFF - j))
+                          : 0ull;   // padding ranks last
+    }
+    tot = wave_sum(tot);
+
+    // 3. bitonic sort, descending by key
+#pragma unroll
+    for (int k = 2; k <= NPAD; k <<= 1) {
+#pragma unroll
+        for (int jj = k >> 1; jj > 0; jj >>= 1) {
+            if (jj < EPL) {
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) {
+                    if (e & jj) continue;
+                    const bool desc = k < EPL ? ((e & k) == 0) : (((lane * EPL) & k) == 0);
+                    const unsigned long long a = key[e], b2 = key[e | jj];
+                    const bool a_first = a > b2;
+                    if (a_first != desc) { key[e] = b2; key[e | jj] = a; }
+                }
+            } else {
+                const int ld = jj / EPL;                      // partner lane = lane ^ ld
+                const int paddr = (lane ^ ld) << 2;           // its byte address for ds_bpermute
+                const bool upper = (lane & ld) != 0;          // this lane holds the later ranks of the pairs
+                const bool desc = ((lane * EPL) & k) == 0;
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) {
+                    const unsigned long long mine = key[e];
+                    const int plo = __builtin_amdgcn_ds_bpermute(paddr, static_cast<int>(mine & 0xFFFFFFFFull));
+                    const int phi = __builtin_amdgcn_ds_bpermute(paddr, static_cast<int>(mine >> 32));
+                    const unsigned long long other = (static_cast<unsigned long long>(static_cast<unsigned>(phi)) << 32) |
+                                                     static_cast<unsigned>(plo);
+                    // the earlier rank of a pair keeps the larger key when the run descends, the later rank the smaller
+                    const bool want_max = desc != upper;
+                    const bool take_other = want_max ? (other > mine) : (other < mine);
+                    key[e] = take_other ? other : mine;
+                }
+            }
+        }
+    }
+
+    // 4. exclusive prefix mass per rank (exact probabilities by index); rank kept iff mass before it < tau * total
+    double pv[EPL];
+    double local = 0.0;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+        pv[e] = key[e] ? pval[wave][0xFFFF - static_cast<int>(key[e] & 0xFFFFull)] : 0.0;
+        local += pv[e];
+    }
+    double incl = local;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const double o = shfl_up_f64(incl, d);
+        if (lane >= d) incl += o;
+    }
+    double before = incl - local;
+    const double thresh = tau * tot;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+        if (pv[e] > 0.0 && before < thresh) flag[wave][0xFFFF - static_cast<int>(key[e] & 0xFFFFull)] = 1;
+        before += pv[e];
+    }
+    __builtin_amdgcn_wave_barrier();   // the flags are read back by other lanes of this wave only
+
+    // 5. fix-block overrides and causal rules, then the row goes out
+    for (int j = lane; j < s.Tn; j += 64) {
+        uint8_t m = flag[wave][j];
+        if (sk[j] < theta) m = 1;
+        if (causal) {
+            if (j * BK > i * BQ + (BQ - 1)) m = 0;
+            if (j == (i * BQ) / BK) m = 1;
+        }
+        out[j] = m;
+    }
+}
+
 }  // namespace
 
 hipError_t launch_logits(const double* pooled_q, const double* ksum_t, const Shape& s, float sm_scale,
@@ -247,6 +390,16 @@ hipError_t launch_logits(const double* pooled_q, const double* ksum_t, const Sha
 hipError_t launch_topcdf(const double* logits, const double* sim_q, const double* sim_k, const Shape& s,
                          const HeadParams& tau, const HeadParams& theta, int causal, uint8_t* mask,
                          hipStream_t st) {
+    const int n_rows = s.B * s.H * s.Tm;
+#define CALLW(EPL)                                                                                                 \
+    hipLaunchKernelGGL((topcdf_wave_kernel<EPL>), dim3((n_rows + 3) / 4), dim3(256), 0, st, logits, sim_q, sim_k, s, \
+                       tau, theta, causal, n_rows, mask)
+    if (s.Tn <= 256) { CALLW(4); return hipGetLastError(); }
+    if (s.Tn <= 512) { CALLW(8); return hipGetLastError(); }
+    if (s.Tn <= 1024) { CALLW(16); return hipGetLastError(); }
+    if (s.Tn <= 2048) { CALLW(32); return hipGetLastError(); }
+#undef CALLW
+    // longer rows: one workgroup per row, sorted in LDS
     int npad = 2;
     while (npad < s.Tn) npad <<= 1;
     const size_t smem = static_cast<size_t>(npad) * (sizeof(double) + sizeof(unsigned long long) + 1);

@@ -160,3 +160,19 @@ def test_long_list_two_stage_kernel(sp, causal, dtype, d, pv_fp8):
         for i in range(Tm):
             visible[i, np.arange(Tn) * 64 > i * 128 + 127] = False
     assert s[0] == visible.sum()
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_predict_long_rows(sp, causal):
+    """T_n in (1024, 2048]: the widest per-wave TopCdf variant (32 ranks per lane).  N = 70 000, one head."""
+    from tests.helpers import small_workload
+    w = small_workload(name="longpred", N=70000, d=64, dtype="bf16", H=1, causal=causal, seed=21, segment=448, noise=0.4)
+    x = make_workload(w)
+    Q, K = (to_torch(x[t], w.dtype) for t in "qk")
+    for tau, theta in ((0.9, 0.5), (0.6, -1.0)):
+        mask = sp.sparge_predict(Q, K, tau, theta, causal=causal).cpu().numpy()
+        pr = so.predict(x["q"][0, 0], x["k"][0, 0], f32(tau), f32(theta), causal=causal)
+        bad = (mask[0, 0] != pr.mask) & ~pr.dont_care
+        print(f"  causal={causal} tau={tau} theta={theta}: kept {mask.mean():.3f}, dont-care {int(pr.dont_care.sum())}", flush=True)
+        assert not bad.any(), np.argwhere(bad)[:5]
+        assert pr.dont_care.mean() < 0.01
