@@ -9,6 +9,8 @@
 // channels for all its rows, which makes channel sums per-lane accumulations.
 #include "common.hpp"
 
+#include <type_traits>
+
 namespace sparge {
 
 namespace {
@@ -18,6 +20,83 @@ __device__ __forceinline__ double shfl_xor_f64(double v, int mask) {
     lo = __shfl_xor(lo, mask);
     hi = __shfl_xor(hi, mask);
     return __hiloint2double(hi, lo);
+}
+
+// Cross-lane reductions on the vector ALU (DPP row operations and the lane-swap instructions) instead of
+// ds_bpermute: the block statistics spend their time in the LDS pipeline otherwise.
+//   PARTNER 1, 2, 8: the value of lane ^ PARTNER (quad permutes, rotation by 8 inside a row of 16).
+//   PARTNER 4: the value of lane 7 - (lane % 8) of the same group of 8, PARTNER 12: of lane 15 - lane % 16 of
+//   the same row (mirrors).  In a reduction whose groups of 4 (of 8) already agree they serve as ^4 (^8).
+template <int PARTNER>
+__device__ __forceinline__ uint32_t row_xchg(uint32_t v) {
+    constexpr int CTRL = PARTNER == 1 ? 0xB1 : PARTNER == 2 ? 0x4E : PARTNER == 4 ? 0x141 : PARTNER == 12 ? 0x140 : 0x128;
+    static_assert(PARTNER == 1 || PARTNER == 2 || PARTNER == 4 || PARTNER == 8 || PARTNER == 12, "no such exchange");
+    return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, 0xF, 0xF, false));
+}
+// {own, partner's} in some order for the lanes ^16 or ^32: v_permlane16_swap / v_permlane32_swap of a register
+// with its copy leave one of the two values in each result, which is all a commutative reduction needs
+template <int PARTNER>
+__device__ __forceinline__ void swap_pair(uint32_t v, uint32_t& a, uint32_t& b) {
+    static_assert(PARTNER == 16 || PARTNER == 32, "no such exchange");
+    if constexpr (PARTNER == 16) {
+        const auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+        a = r[0], b = r[1];
+    } else {
+        const auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+        a = r[0], b = r[1];
+    }
+}
+// v + (v of the partner lane)
+template <int PARTNER>
+__device__ __forceinline__ double add_partner(double v) {
+    const uint32_t lo = static_cast<uint32_t>(__double2loint(v)), hi = static_cast<uint32_t>(__double2hiint(v));
+    if constexpr (PARTNER == 16 || PARTNER == 32) {
+        uint32_t l0, l1, h0, h1;
+        swap_pair<PARTNER>(lo, l0, l1);
+        swap_pair<PARTNER>(hi, h0, h1);
+        return __hiloint2double(static_cast<int>(h0), static_cast<int>(l0)) +
+               __hiloint2double(static_cast<int>(h1), static_cast<int>(l1));
+    } else {
+        return v + __hiloint2double(static_cast<int>(row_xchg<PARTNER>(hi)), static_cast<int>(row_xchg<PARTNER>(lo)));
+    }
+}
+template <int PARTNER>
+__device__ __forceinline__ float max_partner(float v) {
+    if constexpr (PARTNER == 16 || PARTNER == 32) {
+        uint32_t a, b;
+        swap_pair<PARTNER>(__float_as_uint(v), a, b);
+        return fmaxf(__uint_as_float(a), __uint_as_float(b));
+    } else {
+        return fmaxf(v, __uint_as_float(row_xchg<PARTNER>(__float_as_uint(v))));
+    }
+}
+// v summed (maximized) over the aligned group of G lanes, G = 8, 16 or 64; every lane gets the result
+template <int G>
+__device__ __forceinline__ double group_sum(double v) {
+    v = add_partner<1>(v);
+    v = add_partner<2>(v);
+    v = add_partner<4>(v);
+    if constexpr (G >= 16) v = add_partner<12>(v);
+    if constexpr (G == 64) {
+        v = add_partner<16>(v);
+        v = add_partner<32>(v);
+    }
+    return v;
+}
+template <int G>
+__device__ __forceinline__ float group_max(float v) {
+    v = max_partner<1>(v);
+    v = max_partner<2>(v);
+    v = max_partner<4>(v);
+    if constexpr (G >= 16) v = max_partner<12>(v);
+    return v;
+}
+// step(M) for the lane-number bits M = LPR .. 32 (LPR = 8 or 16)
+template <int LPR, typename F>
+__device__ __forceinline__ void across_groups(F&& step) {
+    if constexpr (LPR == 8) step(std::integral_constant<int, 8>{});
+    step(std::integral_constant<int, 16>{});
+    step(std::integral_constant<int, 32>{});
 }
 
 template <int DT>
@@ -91,11 +170,10 @@ __global__ __launch_bounds__(256) void block_stats_kernel(const uint16_t* __rest
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const double x = static_cast<double>(f[e]);
-            nsq += x * x;
+            nsq = __builtin_fma(x, x, nsq);  // x * x is exact in fp64 (16-bit inputs): same result as mul + add
             amax = fmaxf(amax, fabsf(f[e]));
         }
-#pragma unroll
-        for (int m = 1; m < LPR; m <<= 1) nsq += shfl_xor_f64(nsq, m);
+        nsq = group_sum<LPR>(nsq);
         if (cchunk == 0) lds_inv[wave][n * RPW + rsub] = nsq;
     }
     // 1 / |row|: the fp64 square root and division are the expensive part, so each row's is evaluated by
@@ -117,21 +195,20 @@ __global__ __launch_bounds__(256) void block_stats_kernel(const uint16_t* __rest
         for (int e = 0; e < 8; ++e) {
             const double x = static_cast<double>(f[e]);
             sraw[e] += x;
-            shat[e] += x * inv;
+            shat[e] = __builtin_fma(x, inv, shat[e]);
         }
     }
     // combine lanes that hold the same channels (different rows of the wave-wide load)
-#pragma unroll
-    for (int m = LPR; m < 64; m <<= 1) {
+    across_groups<LPR>([&](auto m) {
+        constexpr int M = decltype(m)::value;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            sraw[e] += shfl_xor_f64(sraw[e], m);
-            shat[e] += shfl_xor_f64(shat[e], m);
+            sraw[e] = add_partner<M>(sraw[e]);
+            shat[e] = add_partner<M>(shat[e]);
         }
-        amax = fmaxf(amax, __shfl_xor(amax, m));
-    }
-#pragma unroll
-    for (int m = 1; m < LPR; m <<= 1) amax = fmaxf(amax, __shfl_xor(amax, m));
+        amax = max_partner<M>(amax);
+    });
+    amax = group_max<LPR>(amax);
     if (rsub == 0) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -151,8 +228,7 @@ __global__ __launch_bounds__(256) void block_stats_kernel(const uint16_t* __rest
         if (KSIDE) pooled[(bh * D + c) * T + t] = rsum;
         else pooled[(bh * T + t) * D + c] = rsum / static_cast<double>(cnt);
         double sq = hsum * hsum;
-#pragma unroll
-        for (int m = 1; m < 64; m <<= 1) sq += shfl_xor_f64(sq, m);
+        sq = group_sum<64>(sq);
         if (lane == 0) lds_sq[wave] = sq;
     }
     __syncthreads();
