@@ -9,8 +9,6 @@
 // channels for all its rows, which makes channel sums per-lane accumulations.
 #include "common.hpp"
 
-#include <type_traits>
-
 namespace sparge {
 
 namespace {
@@ -25,13 +23,22 @@ __device__ __forceinline__ double shfl_xor_f64(double v, int mask) {
 // Cross-lane reductions on the vector ALU (DPP row operations and the lane-swap instructions) instead of
 // ds_bpermute: the block statistics spend their time in the LDS pipeline otherwise.
 //   PARTNER 1, 2, 8: the value of lane ^ PARTNER (quad permutes, rotation by 8 inside a row of 16).
-//   PARTNER 4: the value of lane 7 - (lane % 8) of the same group of 8, PARTNER 12: of lane 15 - lane % 16 of
-//   the same row (mirrors).  In a reduction whose groups of 4 (of 8) already agree they serve as ^4 (^8).
+//   PARTNER 4: the value of lane ^ 4 (two shifts by 4, each written to the banks it is right for).
+//   PARTNER 7, 15: the value of lane 7 - lane % 8 of the same group of 8, of lane 15 - lane % 16 of the same
+//   row (mirrors, one instruction).  They serve as ^4 (^8) ONLY where the lanes of each group of 4 (of 8)
+//   already hold the same value.
 template <int PARTNER>
 __device__ __forceinline__ uint32_t row_xchg(uint32_t v) {
-    constexpr int CTRL = PARTNER == 1 ? 0xB1 : PARTNER == 2 ? 0x4E : PARTNER == 4 ? 0x141 : PARTNER == 12 ? 0x140 : 0x128;
-    static_assert(PARTNER == 1 || PARTNER == 2 || PARTNER == 4 || PARTNER == 8 || PARTNER == 12, "no such exchange");
-    return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, 0xF, 0xF, false));
+    static_assert(PARTNER == 1 || PARTNER == 2 || PARTNER == 4 || PARTNER == 8 || PARTNER == 7 || PARTNER == 15,
+                  "no such exchange");
+    if constexpr (PARTNER == 4) {
+        // row_shl:4 brings lane + 4 (banks 0 and 2 take it), row_shr:4 brings lane - 4 (banks 1 and 3)
+        const int up = __builtin_amdgcn_update_dpp(0, static_cast<int>(v), 0x104, 0xF, 0x5, false);
+        return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(up, static_cast<int>(v), 0x114, 0xF, 0xA, false));
+    } else {
+        constexpr int CTRL = PARTNER == 1 ? 0xB1 : PARTNER == 2 ? 0x4E : PARTNER == 7 ? 0x141 : PARTNER == 15 ? 0x140 : 0x128;
+        return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, 0xF, 0xF, false));
+    }
 }
 // {own, partner's} in some order for the lanes ^16 or ^32: v_permlane16_swap / v_permlane32_swap of a register
 // with its copy leave one of the two values in each result, which is all a commutative reduction needs
@@ -70,13 +77,43 @@ __device__ __forceinline__ float max_partner(float v) {
         return fmaxf(v, __uint_as_float(row_xchg<PARTNER>(__float_as_uint(v))));
     }
 }
+// Two values reduced at the price of one: the lanes whose number has bit PARTNER clear end up with
+// a + (a of lane ^ PARTNER), the others with b + (b of lane ^ PARTNER).
+template <int PARTNER>
+__device__ __forceinline__ double scatter_sum(double a, double b) {
+    if constexpr (PARTNER == 16 || PARTNER == 32) {
+        // the swap moves a's upper half (odd rows) against b's lower half (even rows): no copies, no selects
+        uint32_t l0, l1, h0, h1;
+        if constexpr (PARTNER == 16) {
+            const auto rl = __builtin_amdgcn_permlane16_swap(static_cast<uint32_t>(__double2loint(a)),
+                                                             static_cast<uint32_t>(__double2loint(b)), false, false);
+            const auto rh = __builtin_amdgcn_permlane16_swap(static_cast<uint32_t>(__double2hiint(a)),
+                                                             static_cast<uint32_t>(__double2hiint(b)), false, false);
+            l0 = rl[0], l1 = rl[1], h0 = rh[0], h1 = rh[1];
+        } else {
+            const auto rl = __builtin_amdgcn_permlane32_swap(static_cast<uint32_t>(__double2loint(a)),
+                                                             static_cast<uint32_t>(__double2loint(b)), false, false);
+            const auto rh = __builtin_amdgcn_permlane32_swap(static_cast<uint32_t>(__double2hiint(a)),
+                                                             static_cast<uint32_t>(__double2hiint(b)), false, false);
+            l0 = rl[0], l1 = rl[1], h0 = rh[0], h1 = rh[1];
+        }
+        return __hiloint2double(static_cast<int>(h0), static_cast<int>(l0)) +
+               __hiloint2double(static_cast<int>(h1), static_cast<int>(l1));
+    } else {
+        static_assert(PARTNER == 1 || PARTNER == 2, "a true lane ^ PARTNER exchange is needed here");
+        const bool up = (threadIdx.x & PARTNER) != 0;
+        const double keep = up ? b : a, send = up ? a : b;
+        return keep + __hiloint2double(static_cast<int>(row_xchg<PARTNER>(static_cast<uint32_t>(__double2hiint(send)))),
+                                       static_cast<int>(row_xchg<PARTNER>(static_cast<uint32_t>(__double2loint(send)))));
+    }
+}
 // v summed (maximized) over the aligned group of G lanes, G = 8, 16 or 64; every lane gets the result
 template <int G>
 __device__ __forceinline__ double group_sum(double v) {
     v = add_partner<1>(v);
     v = add_partner<2>(v);
-    v = add_partner<4>(v);
-    if constexpr (G >= 16) v = add_partner<12>(v);
+    v = add_partner<7>(v);  // the quads agree by now: the mirrors do
+    if constexpr (G >= 16) v = add_partner<15>(v);
     if constexpr (G == 64) {
         v = add_partner<16>(v);
         v = add_partner<32>(v);
@@ -87,18 +124,10 @@ template <int G>
 __device__ __forceinline__ float group_max(float v) {
     v = max_partner<1>(v);
     v = max_partner<2>(v);
-    v = max_partner<4>(v);
-    if constexpr (G >= 16) v = max_partner<12>(v);
+    v = max_partner<7>(v);
+    if constexpr (G >= 16) v = max_partner<15>(v);
     return v;
 }
-// step(M) for the lane-number bits M = LPR .. 32 (LPR = 8 or 16)
-template <int LPR, typename F>
-__device__ __forceinline__ void across_groups(F&& step) {
-    if constexpr (LPR == 8) step(std::integral_constant<int, 8>{});
-    step(std::integral_constant<int, 16>{});
-    step(std::integral_constant<int, 32>{});
-}
-
 template <int DT>
 __device__ __forceinline__ void unpack8(const uint4& raw, float (&f)[8]) {
     const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
@@ -162,19 +191,42 @@ __global__ __launch_bounds__(256) void block_stats_kernel(const uint16_t* __rest
     for (int e = 0; e < 8; ++e) sraw[e] = shat[e] = 0.0;
     float amax = 0.f;
     // squared norm of every row of this wave (NL * RPW of them), one value per row in LDS
+    double nsq[NL];
 #pragma unroll
     for (int n = 0; n < NL; ++n) {
         float f[8];
         unpack8<DT>(raw[n], f);
-        double nsq = 0.0;
+        nsq[n] = 0.0;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const double x = static_cast<double>(f[e]);
-            nsq = __builtin_fma(x, x, nsq);  // x * x is exact in fp64 (16-bit inputs): same result as mul + add
+            nsq[n] = __builtin_fma(x, x, nsq[n]);  // x * x is exact in fp64 (16-bit inputs): same result as mul + add
             amax = fmaxf(amax, fabsf(f[e]));
         }
-        nsq = group_sum<LPR>(nsq);
-        if (cchunk == 0) lds_inv[wave][n * RPW + rsub] = nsq;
+    }
+    // The LPR lanes of a row are summed with the first steps halving the number of values: after them
+    // the lane with bits (p, q) = (lane & 1, lane >> 1 & 1) works on the rows n = i + NQ q + NH p only.
+    {
+        static_assert(NL == 2 || NL == 4 || NL == 8, "row count per lane");
+        constexpr int NH = NL / 2, NQ = NL >= 4 ? NL / 4 : 1;
+        double w1[NH];
+#pragma unroll
+        for (int i = 0; i < NH; ++i) w1[i] = scatter_sum<1>(nsq[i], nsq[i + NH]);
+        const int p = lane & 1, q = (lane >> 1) & 1;
+        if constexpr (NL >= 4) {
+#pragma unroll
+            for (int i = 0; i < NQ; ++i) {
+                double w = scatter_sum<2>(w1[i], w1[i + NQ]);
+                w = add_partner<4>(w);  // lanes of a quad hold different rows from here on: true ^4, ^8 only
+                if constexpr (LPR == 16) w = add_partner<8>(w);
+                if (cchunk < 4) lds_inv[wave][(i + NQ * q + NH * p) * RPW + rsub] = w;
+            }
+        } else {
+            double w = add_partner<2>(w1[0]);
+            w = add_partner<4>(w);
+            if constexpr (LPR == 16) w = add_partner<8>(w);
+            if (cchunk < 2) lds_inv[wave][p * RPW + rsub] = w;
+        }
     }
     // 1 / |row|: the fp64 square root and division are the expensive part, so each row's is evaluated by
     // one lane only (a wave owns at most 64 rows) and handed to the lanes of that row through LDS
@@ -198,22 +250,28 @@ __global__ __launch_bounds__(256) void block_stats_kernel(const uint16_t* __rest
             shat[e] = __builtin_fma(x, inv, shat[e]);
         }
     }
-    // combine lanes that hold the same channels (different rows of the wave-wide load)
-    across_groups<LPR>([&](auto m) {
-        constexpr int M = decltype(m)::value;
+    // Combine the lanes that hold the same channels (different rows of the wave-wide load).  Lane bits 5
+    // and 4 each halve the 16 sums a lane works on: lane bit 5 selects raw sums / normalized sums, lane
+    // bit 4 the channels 0..3 / 4..7 of the lane's chunk.  (d = 64: lane bit 3 is reduced last, in full.)
+    {
+        double h8[8], h4[4];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            sraw[e] = add_partner<M>(sraw[e]);
-            shat[e] = add_partner<M>(shat[e]);
+        for (int e = 0; e < 8; ++e) h8[e] = scatter_sum<32>(sraw[e], shat[e]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) h4[e] = scatter_sum<16>(h8[e], h8[e + 4]);
+        if constexpr (LPR == 8) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) h4[e] = add_partner<8>(h4[e]);
         }
-        amax = max_partner<M>(amax);
-    });
-    amax = group_max<LPR>(amax);
-    if (rsub == 0) {
+        amax = max_partner<32>(amax);
+        amax = max_partner<16>(amax);
+        if constexpr (LPR == 8) amax = max_partner<8>(amax);
+        amax = group_max<LPR>(amax);
+        if (LPR == 16 || (lane & 8) == 0) {
+            double* dst = (lane & 32) ? lds_hat[wave] : lds_raw[wave];
+            const int c0 = cchunk * 8 + ((lane & 16) ? 4 : 0);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            lds_raw[wave][cchunk * 8 + e] = sraw[e];
-            lds_hat[wave][cchunk * 8 + e] = shat[e];
+            for (int e = 0; e < 4; ++e) dst[c0 + e] = h4[e];
         }
     }
     if (lane == 0) lds_amax[wave] = amax;
