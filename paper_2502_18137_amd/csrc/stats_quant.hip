@@ -139,13 +139,18 @@ __device__ __forceinline__ void unpack8(const uint4& raw, float (&f)[8]) {
 }
 
 // x_hat = rint_half_even(x * r) packed as 8 int8 (fp32 multiply, single rounding, no contraction).
+// Adding 1.5 * 2^23 to the rounded product rounds it to an integer, to nearest even, and leaves that
+// integer in two's complement in the low mantissa bits (|x * r| <= 127): the low byte is x_hat.
 __device__ __forceinline__ uint2 quant8(const float (&f)[8], float r) {
-    uint32_t out[2] = {0u, 0u};
+    uint32_t y[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        float y = __builtin_rintf(f[e] * r);
-        int q = static_cast<int>(y);
-        out[e >> 2] |= (static_cast<uint32_t>(q) & 0xFFu) << (8 * (e & 3));
+    for (int e = 0; e < 8; ++e) y[e] = __float_as_uint(f[e] * r + 12582912.0f);
+    uint32_t out[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const uint32_t lo = __builtin_amdgcn_perm(y[4 * h + 1], y[4 * h + 0], 0x0c0c0400u);  // bytes {y0, y1, 0, 0}
+        const uint32_t hi = __builtin_amdgcn_perm(y[4 * h + 3], y[4 * h + 2], 0x0c0c0400u);
+        out[h] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
     }
     return make_uint2(out[0], out[1]);
 }
