@@ -1,9 +1,11 @@
 // C ABI of libsparge: argument validation, workspace partition, kernel sequencing.
-// Nothing here allocates or synchronises; every kernel goes onto the caller's stream.
+// Nothing here allocates device memory or synchronises; every kernel goes onto the caller's stream, except
+// that sparge_forward runs three passes on a second stream between a fork and a join on the caller's.
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "common.hpp"
@@ -157,6 +159,40 @@ int check_lambda(const float* lambda, int H, HeadParams* l) {
 }
 
 // Block statistics of Q and K, Q quantization, K mean, K quantization (any output may be skipped).
+// A second stream per device (default priority) with the two events of a fork and join.  The forward
+// pass puts the passes nobody waits for early (K mean, K quantization, V tiles: bandwidth-bound) there,
+// beside the block predictor (fp64 matrix products and a sort: neither bandwidth-bound), and joins before
+// the attention kernel.  Created on first use, kept until the process ends; no second stream (creation
+// failed, or more devices than slots) means everything runs on the caller's stream.
+struct SideStream {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+    bool tried = false;
+};
+constexpr int MAX_DEVICES = 64;
+SideStream g_side[MAX_DEVICES];
+std::mutex g_side_mutex;
+
+// (call with g_side_mutex held, and keep it until the join is enqueued: the events are shared)
+SideStream* side_stream() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+    SideStream& x = g_side[dev];
+    if (!x.tried) {
+        x.tried = true;
+        hipStream_t st = nullptr;
+        hipEvent_t a = nullptr, b = nullptr;
+        if (hipStreamCreateWithFlags(&st, hipStreamNonBlocking) == hipSuccess &&
+            hipEventCreateWithFlags(&a, hipEventDisableTiming) == hipSuccess &&
+            hipEventCreateWithFlags(&b, hipEventDisableTiming) == hipSuccess) {
+            x.stream = st, x.fork = a, x.join = b;
+        } else {
+            (void)hipGetLastError();  // not an error of the call that asked
+        }
+    }
+    return x.stream ? &x : nullptr;
+}
+
 int run_stats_and_quant(const void* Q, const void* K, const Shape& s, double* pooled_q, double* ksum_t,
                         double* sim_q, double* sim_k, int8_t* Qq, float* q_scale, int8_t* Kq, float* k_scale,
                         float* k_mean, hipStream_t st) {
@@ -360,16 +396,47 @@ int sparge_forward(const void* Q, const void* K, const void* V, const sparge_des
     if ((rc = check_ws(w, ws, ws_bytes))) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const bool q8 = !s.qk16;  // the 16-bit product needs the block statistics only
-    if ((rc = run_stats_and_quant(Q, K, s, at<double>(ws, w.pooled_q), at<double>(ws, w.ksum_t),
-                                  at<double>(ws, w.sim_q), at<double>(ws, w.sim_k), q8 ? at<int8_t>(ws, w.Qq) : nullptr,
-                                  q8 ? at<float>(ws, w.q_scale) : nullptr, q8 ? at<int8_t>(ws, w.Kq) : nullptr,
-                                  at<float>(ws, w.k_scale), at<float>(ws, w.k_mean), st))) return rc;
     uint8_t* mask = mask_out ? mask_out : at<uint8_t>(ws, w.mask);
-    if ((rc = run_predict(s, ws, w, t, th, sm_scale, causal, mask, st))) return rc;
-    if (s.qk16)
-        return run_attn(Q, K, nullptr, nullptr, V, s, at<char>(ws, w.v_tiles), mask, lam, sm_scale, causal, O, stats, st);
-    return run_attn(at<int8_t>(ws, w.Qq), at<int8_t>(ws, w.Kq), at<float>(ws, w.q_scale), at<float>(ws, w.k_scale),
-                    V, s, at<char>(ws, w.v_tiles), mask, lam, sm_scale, causal, O, stats, st);
+    const void* Qa = q8 ? static_cast<const void*>(at<int8_t>(ws, w.Qq)) : Q;
+    const void* Ka = q8 ? static_cast<const void*>(at<int8_t>(ws, w.Kq)) : K;
+    const float* qsc = q8 ? at<float>(ws, w.q_scale) : nullptr;
+    const float* ksc = q8 ? at<float>(ws, w.k_scale) : nullptr;
+    std::lock_guard<std::mutex> lock(g_side_mutex);
+    SideStream* side = side_stream();
+    if (!side) {
+        if ((rc = run_stats_and_quant(Q, K, s, at<double>(ws, w.pooled_q), at<double>(ws, w.ksum_t),
+                                      at<double>(ws, w.sim_q), at<double>(ws, w.sim_k), q8 ? at<int8_t>(ws, w.Qq) : nullptr,
+                                      q8 ? at<float>(ws, w.q_scale) : nullptr, q8 ? at<int8_t>(ws, w.Kq) : nullptr,
+                                      at<float>(ws, w.k_scale), at<float>(ws, w.k_mean), st))) return rc;
+        if ((rc = run_predict(s, ws, w, t, th, sm_scale, causal, mask, st))) return rc;
+        return run_attn(Qa, Ka, qsc, ksc, V, s, at<char>(ws, w.v_tiles), mask, lam, sm_scale, causal, O, stats, st);
+    }
+    // caller's stream: block statistics (+ Q quantization) -> fork -> predictor -> join -> attention
+    // second stream:                                  fork -> K mean, K quantization, V tiles -> join
+    hipError_t e;
+    if ((e = launch_block_stats_q(Q, s, at<double>(ws, w.pooled_q), at<double>(ws, w.sim_q),
+                                  q8 ? at<int8_t>(ws, w.Qq) : nullptr, q8 ? at<float>(ws, w.q_scale) : nullptr, st)) != hipSuccess)
+        return hip_fail(e, "block_stats_q");
+    if ((e = launch_block_stats_k(K, s, at<double>(ws, w.ksum_t), at<double>(ws, w.sim_k), st)) != hipSuccess)
+        return hip_fail(e, "block_stats_k");
+    if ((e = hipEventRecord(side->fork, st)) != hipSuccess) return hip_fail(e, "record fork");
+    if ((e = hipStreamWaitEvent(side->stream, side->fork, 0)) != hipSuccess) return hip_fail(e, "wait fork");
+    // from here on the second stream is joined whatever happens, so that a capture of the caller's stream can end
+    int rc_side = SPARGE_OK;
+    if (q8) {
+        if ((e = launch_k_mean(at<double>(ws, w.ksum_t), s, at<float>(ws, w.k_mean), side->stream)) != hipSuccess)
+            rc_side = hip_fail(e, "k_mean");
+        else if ((e = launch_quant_k(K, s, at<float>(ws, w.k_mean), at<int8_t>(ws, w.Kq), at<float>(ws, w.k_scale),
+                                     side->stream)) != hipSuccess)
+            rc_side = hip_fail(e, "quant_k");
+    }
+    if (!rc_side && (e = retile_v(V, s, at<char>(ws, w.v_tiles), side->stream)) != hipSuccess) rc_side = hip_fail(e, "v_tiles");
+    rc = rc_side ? SPARGE_OK : run_predict(s, ws, w, t, th, sm_scale, causal, mask, st);
+    if ((e = hipEventRecord(side->join, side->stream)) != hipSuccess) return hip_fail(e, "record join");
+    if ((e = hipStreamWaitEvent(st, side->join, 0)) != hipSuccess) return hip_fail(e, "wait join");
+    if (rc_side) return rc_side;
+    if (rc) return rc;
+    return timed_attn(Qa, Ka, qsc, ksc, at<char>(ws, w.v_tiles), s, mask, lam, sm_scale, causal, O, stats, st);
 }
 
 int sparge_rel_l1(const void* O, const void* O_ref, const sparge_desc* desc, double* out, void* hip_stream) {
