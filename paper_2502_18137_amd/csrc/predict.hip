@@ -44,7 +44,7 @@ __global__ __launch_bounds__(256) void logits_kernel(const double* __restrict__ 
     v4d acc[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) acc[t] = v4d{0.0, 0.0, 0.0, 0.0};
-#pragma unroll 4
+#pragma unroll
     for (int c = 0; c < D; c += 4) {
         const double a = qrow[c];
 #pragma unroll
