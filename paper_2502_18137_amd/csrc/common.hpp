@@ -32,6 +32,26 @@ typedef float v8f __attribute__((ext_vector_type(8)));
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
+// The value another lane of the same row of 16 holds, through a DPP move (vector ALU, no LDS traffic).
+//   PARTNER 1, 2, 8: the value of lane ^ PARTNER (quad permutes, rotation by 8 inside a row of 16).
+//   PARTNER 4: the value of lane ^ 4 (two shifts by 4, each written to the banks it is right for).
+//   PARTNER 7, 15: the value of lane 7 - lane % 8 of the same group of 8, of lane 15 - lane % 16 of the same
+//   row (mirrors, one instruction).  They serve as ^4 (^8) ONLY where the lanes of each group of 4 (of 8)
+//   already hold the same value.
+template <int PARTNER>
+__device__ __forceinline__ uint32_t row_xchg(uint32_t v) {
+    static_assert(PARTNER == 1 || PARTNER == 2 || PARTNER == 4 || PARTNER == 8 || PARTNER == 7 || PARTNER == 15,
+                  "no such exchange");
+    if constexpr (PARTNER == 4) {
+        // row_shl:4 brings lane + 4 (banks 0 and 2 take it), row_shr:4 brings lane - 4 (banks 1 and 3)
+        const int up = __builtin_amdgcn_update_dpp(0, static_cast<int>(v), 0x104, 0xF, 0x5, false);
+        return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(up, static_cast<int>(v), 0x114, 0xF, 0xA, false));
+    } else {
+        constexpr int CTRL = PARTNER == 1 ? 0xB1 : PARTNER == 2 ? 0x4E : PARTNER == 7 ? 0x141 : PARTNER == 15 ? 0x140 : 0x128;
+        return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, 0xF, 0xF, false));
+    }
+}
+
 // 16-bit storage -> fp32 (exact).  DT: SPARGE_F16 or SPARGE_BF16.
 template <int DT>
 __device__ __forceinline__ float cvt16(uint16_t bits) {

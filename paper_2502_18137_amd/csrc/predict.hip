@@ -233,11 +233,90 @@ __global__ __launch_bounds__(256) void topcdf_kernel(const double* __restrict__ 
     }
 }
 
+// v_permlane16_swap (LD = 16: odd rows of 16 lanes of a against even rows of b) or v_permlane32_swap (LD = 32:
+// upper half of a against lower half of b); applying it twice restores a and b
+template <int LD>
+__device__ __forceinline__ void lane_swap(uint32_t a, uint32_t b, uint32_t& a_out, uint32_t& b_out) {
+    static_assert(LD == 16 || LD == 32, "no such swap");
+    if constexpr (LD == 16) {
+        const auto r = __builtin_amdgcn_permlane16_swap(a, b, false, false);
+        a_out = r[0], b_out = r[1];
+    } else {
+        const auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
+        a_out = r[0], b_out = r[1];
+    }
+}
+
+// Bitonic sort, descending, of 64 * EPL keys held EPL consecutive ranks per lane.  The stages are
+// instantiated one by one (K: length of the runs being merged, JJ: distance of the pairs), so that every
+// register index, DPP control and swap is a compile-time constant.
+template <int EPL, int K, int JJ>
+__device__ __forceinline__ void bitonic_stage(unsigned long long (&key)[EPL], int lane) {
+    if constexpr (JJ < EPL) {  // both members of a pair in this lane
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+            if (e & JJ) continue;
+            const bool desc = K < EPL ? ((e & K) == 0) : (((lane * EPL) & K) == 0);
+            const unsigned long long a = key[e], b = key[e | JJ];
+            const bool exch = (a > b) != desc;
+            key[e] = exch ? b : a;
+            key[e | JJ] = exch ? a : b;
+        }
+    } else {
+        constexpr int LD = JJ / EPL;  // partner lane = lane ^ LD
+        const bool desc = ((lane * EPL) & K) == 0;
+        if constexpr (LD >= 16) {
+            // Lanes 16 or 32 apart: the lane swap of the keys of two entries e, e+1 puts both members of a pair
+            // into one lane (one half of the lanes gets the pairs of entry e, the other half those of entry
+            // e+1, earlier rank first); the pair is ordered there like a pair inside a lane, and the same swap
+            // takes the keys home.
+#pragma unroll
+            for (int e = 0; e < EPL; e += 2) {
+                uint32_t al, ah, bl, bh;
+                lane_swap<LD>(static_cast<uint32_t>(key[e]), static_cast<uint32_t>(key[e + 1]), al, bl);
+                lane_swap<LD>(static_cast<uint32_t>(key[e] >> 32), static_cast<uint32_t>(key[e + 1] >> 32), ah, bh);
+                const unsigned long long a = (static_cast<unsigned long long>(ah) << 32) | al;
+                const unsigned long long b = (static_cast<unsigned long long>(bh) << 32) | bl;
+                const bool exch = (a > b) != desc;
+                const unsigned long long first = exch ? b : a, second = exch ? a : b;
+                lane_swap<LD>(static_cast<uint32_t>(first), static_cast<uint32_t>(second), al, bl);
+                lane_swap<LD>(static_cast<uint32_t>(first >> 32), static_cast<uint32_t>(second >> 32), ah, bh);
+                key[e] = (static_cast<unsigned long long>(ah) << 32) | al;
+                key[e + 1] = (static_cast<unsigned long long>(bh) << 32) | bl;
+            }
+        } else {
+            // closer lanes: the partner's key comes through DPP moves
+            const bool upper = (lane & LD) != 0;  // this lane holds the later ranks of the pairs
+            // the earlier rank of a pair keeps the larger key when the run descends, the later rank the smaller
+            const bool want_max = desc != upper;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) {
+                const unsigned long long mine = key[e];
+                const uint32_t plo = row_xchg<LD>(static_cast<uint32_t>(mine));
+                const uint32_t phi = row_xchg<LD>(static_cast<uint32_t>(mine >> 32));
+                const unsigned long long other = (static_cast<unsigned long long>(phi) << 32) | plo;
+                const bool take_other = want_max ? (other > mine) : (other < mine);
+                key[e] = take_other ? other : mine;
+            }
+        }
+    }
+}
+template <int EPL, int K, int JJ>
+__device__ __forceinline__ void bitonic_merge(unsigned long long (&key)[EPL], int lane) {
+    bitonic_stage<EPL, K, JJ>(key, lane);
+    if constexpr (JJ > 1) bitonic_merge<EPL, K, JJ / 2>(key, lane);
+}
+template <int EPL, int K = 2>
+__device__ __forceinline__ void bitonic_sort(unsigned long long (&key)[EPL], int lane) {
+    bitonic_merge<EPL, K, K / 2>(key, lane);
+    if constexpr (K < 64 * EPL) bitonic_sort<EPL, 2 * K>(key, lane);
+}
+
 // TopCdf with one mask row per wave and the sort in registers: lane L holds the EPL consecutive ranks
 // L * EPL .. L * EPL + EPL - 1 as 64-bit keys (see topcdf_kernel for the key).  A bitonic stage at a distance
 // below EPL exchanges inside a lane (compile-time register indices), a larger one takes the partner
-// lane's key with a shuffle; nothing but the final flags and the exact probabilities goes through LDS,
-// and no workgroup barrier is needed.  Same comparisons, hence the same order, as the LDS version.
+// lane's key with DPP moves or lane swaps (vector ALU: with ds_bpermute the LDS pipeline was the limit);
+// nothing but the final flags and the exact probabilities goes through LDS, and no workgroup barrier is needed.  Same comparisons, hence the same order, as the LDS version.
 template <int EPL>
 __global__ __launch_bounds__(256) void topcdf_wave_kernel(const double* __restrict__ logits,
                                                            const double* __restrict__ sim_q,
@@ -307,39 +386,7 @@ __global__ __launch_bounds__(256) void topcdf_wave_kernel(const double* __restri
     tot = wave_sum(tot);
 
     // 3. bitonic sort, descending by key
-#pragma unroll
-    for (int k = 2; k <= NPAD; k <<= 1) {
-#pragma unroll
-        for (int jj = k >> 1; jj > 0; jj >>= 1) {
-            if (jj < EPL) {
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) {
-                    if (e & jj) continue;
-                    const bool desc = k < EPL ? ((e & k) == 0) : (((lane * EPL) & k) == 0);
-                    const unsigned long long a = key[e], b2 = key[e | jj];
-                    const bool a_first = a > b2;
-                    if (a_first != desc) { key[e] = b2; key[e | jj] = a; }
-                }
-            } else {
-                const int ld = jj / EPL;                      // partner lane = lane ^ ld
-                const int paddr = (lane ^ ld) << 2;           // its byte address for ds_bpermute
-                const bool upper = (lane & ld) != 0;          // this lane holds the later ranks of the pairs
-                const bool desc = ((lane * EPL) & k) == 0;
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) {
-                    const unsigned long long mine = key[e];
-                    const int plo = __builtin_amdgcn_ds_bpermute(paddr, static_cast<int>(mine & 0xFFFFFFFFull));
-                    const int phi = __builtin_amdgcn_ds_bpermute(paddr, static_cast<int>(mine >> 32));
-                    const unsigned long long other = (static_cast<unsigned long long>(static_cast<unsigned>(phi)) << 32) |
-                                                     static_cast<unsigned>(plo);
-                    // the earlier rank of a pair keeps the larger key when the run descends, the later rank the smaller
-                    const bool want_max = desc != upper;
-                    const bool take_other = want_max ? (other > mine) : (other < mine);
-                    key[e] = take_other ? other : mine;
-                }
-            }
-        }
-    }
+    bitonic_sort<EPL>(key, lane);
 
     // 4. exclusive prefix mass per rank (exact probabilities by index); rank kept iff mass before it < tau * total
     double pv[EPL];
