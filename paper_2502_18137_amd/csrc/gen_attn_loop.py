@@ -393,6 +393,13 @@ def gen_loop(c, NST):
     lines = []
     o = lines.append
     period = 2 * NST if NST % 2 else NST  # bodies: one set per value of u mod lcm(2, NST)
+    # The loop's position relative to the 32-byte instruction fetch lines must not depend on the size of the
+    # code the compiler puts in front of it: at d = 64 (bf16, three stages) a start 20 or 24 bytes into a line
+    # is 2-3 % faster than any other multiple of 4 (measured over all eight of them, twice; d = 128 shows
+    # no difference).  The padding runs once per item.
+    o(".p2align 5")
+    for _ in range(5):
+        o("s_nop 0")
     o(f"s_mov_b32 s{s['negmagic']}, 0x{0 if c.qk16 else MAGIC_NEG:08x}")   # fp32 scores carry no bias
     o(f"s_mov_b32 s{s['rt']}, 0x{RESCALE_T[c.T_LOG2]:08x}")
     o(f"s_cmp_lg_u32 s{s['exec']}, 0")                 # stage-2 decision of tile 0 as a lane mask
