@@ -119,6 +119,10 @@ int sparge_predict(const void* Q, const void* K, const sparge_desc* desc,
  * O: same dtype/strides as V (desc).  stats: optional uint64 [B,H,4] = {QK^T tiles executed,
  * P~V row-group products executed, tiles a full attention needs, row-group products a full
  * attention needs}; it is overwritten, not accumulated.
+ * Work distribution: the launch is two resident workgroups per compute unit that take (head, Q block)
+ * items from counters in a static device array of the library (64 sets, one per launch in rotation,
+ * cleared by a one-wave kernel enqueued in front of the launch).  More than 64 attention launches in
+ * flight at once on one device (other streams) would share a set; results are undefined then.
  */
 int sparge_attn_quantized(const int8_t* Qq, const int8_t* Kq, const float* q_scale, const float* k_scale,
                           const void* V, const sparge_desc* desc, const uint8_t* mask,
