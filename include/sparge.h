@@ -163,7 +163,7 @@ int sparge_attn(const void* Q, const void* K, const void* V, const sparge_desc* 
  * All of Algorithm 1: Quant, predict M_g, masked loop with the lambda skip.  Q and K are each read
  * once for block statistics + Q quantization and K is read a second time for its quantization.
  * mask_out: optional uint8 [B,H,T_m,T_n] receiving M_g (NULL: kept in `ws` only).
- * Streams: the K mean, the K quantization and the V tiles run on a second stream that the library
+ * Streams: the V tiles, the K mean and the K quantization run on a second stream that the library
  * keeps per device (created at the first call on that device, default priority, never destroyed),
  * forked from `hip_stream` after the block statistics and joined to it before the attention kernel,
  * next to the block predictor on `hip_stream`.  For the caller the call is ordered on `hip_stream`

@@ -412,7 +412,7 @@ int sparge_forward(const void* Q, const void* K, const void* V, const sparge_des
         return run_attn(Qa, Ka, qsc, ksc, V, s, at<char>(ws, w.v_tiles), mask, lam, sm_scale, causal, O, stats, st);
     }
     // caller's stream: block statistics (+ Q quantization) -> fork -> predictor -> join -> attention
-    // second stream:                                  fork -> K mean, K quantization, V tiles -> join
+    // second stream:                                  fork -> V tiles, K mean, K quantization -> join
     hipError_t e;
     if ((e = launch_block_stats_q(Q, s, at<double>(ws, w.pooled_q), at<double>(ws, w.sim_q),
                                   q8 ? at<int8_t>(ws, w.Qq) : nullptr, q8 ? at<float>(ws, w.q_scale) : nullptr, st)) != hipSuccess)
@@ -423,14 +423,15 @@ int sparge_forward(const void* Q, const void* K, const void* V, const sparge_des
     if ((e = hipStreamWaitEvent(side->stream, side->fork, 0)) != hipSuccess) return hip_fail(e, "wait fork");
     // from here on the second stream is joined whatever happens, so that a capture of the caller's stream can end
     int rc_side = SPARGE_OK;
-    if (q8) {
+    // V tiles first: they need LDS, which the logits kernel beside them leaves free and TopCdf does not
+    if ((e = retile_v(V, s, at<char>(ws, w.v_tiles), side->stream)) != hipSuccess) rc_side = hip_fail(e, "v_tiles");
+    if (q8 && !rc_side) {
         if ((e = launch_k_mean(at<double>(ws, w.ksum_t), s, at<float>(ws, w.k_mean), side->stream)) != hipSuccess)
             rc_side = hip_fail(e, "k_mean");
         else if ((e = launch_quant_k(K, s, at<float>(ws, w.k_mean), at<int8_t>(ws, w.Kq), at<float>(ws, w.k_scale),
                                      side->stream)) != hipSuccess)
             rc_side = hip_fail(e, "quant_k");
     }
-    if (!rc_side && (e = retile_v(V, s, at<char>(ws, w.v_tiles), side->stream)) != hipSuccess) rc_side = hip_fail(e, "v_tiles");
     rc = rc_side ? SPARGE_OK : run_predict(s, ws, w, t, th, sm_scale, causal, mask, st);
     if ((e = hipEventRecord(side->join, side->stream)) != hipSuccess) return hip_fail(e, "record join");
     if ((e = hipStreamWaitEvent(st, side->join, 0)) != hipSuccess) return hip_fail(e, "wait join");
