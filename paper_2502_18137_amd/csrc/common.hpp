@@ -48,7 +48,9 @@ __device__ __forceinline__ uint32_t row_xchg(uint32_t v) {
         return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(up, static_cast<int>(v), 0x114, 0xF, 0xA, false));
     } else {
         constexpr int CTRL = PARTNER == 1 ? 0xB1 : PARTNER == 2 ? 0x4E : PARTNER == 7 ? 0x141 : PARTNER == 15 ? 0x140 : 0x128;
-        return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, 0xF, 0xF, false));
+        // every lane has a source inside its row; bound_ctrl tells the compiler that the destination's old
+        // value is never kept, which saves a register preload and its wait states per exchange
+        return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, 0xF, 0xF, true));
     }
 }
 
