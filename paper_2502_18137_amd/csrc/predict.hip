@@ -287,16 +287,17 @@ __device__ __forceinline__ void bitonic_stage(unsigned long long (&key)[EPL], in
         } else {
             // closer lanes: the partner's key comes through DPP moves
             const bool upper = (lane & LD) != 0;  // this lane holds the later ranks of the pairs
-            // the earlier rank of a pair keeps the larger key when the run descends, the later rank the smaller
-            const bool want_max = desc != upper;
+            // the earlier rank of a pair keeps the larger key when the run descends, the later rank the smaller:
+            // take the partner's key if it is larger and the larger one is wanted, or neither (equal keys are
+            // padding, either copy will do)
+            const bool want_min = desc == upper;
 #pragma unroll
             for (int e = 0; e < EPL; ++e) {
                 const unsigned long long mine = key[e];
                 const uint32_t plo = row_xchg<LD>(static_cast<uint32_t>(mine));
                 const uint32_t phi = row_xchg<LD>(static_cast<uint32_t>(mine >> 32));
                 const unsigned long long other = (static_cast<unsigned long long>(phi) << 32) | plo;
-                const bool take_other = want_max ? (other > mine) : (other < mine);
-                key[e] = take_other ? other : mine;
+                key[e] = ((other > mine) != want_min) ? other : mine;
             }
         }
     }
