@@ -31,7 +31,7 @@ PEAK_HBM = 8.0e12    # B/s
 # HBM-side bytes per launch of the attention kernel (read + written), from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs of this script scaled by a 1 GiB copy (profiles/attn_kernel_hbm_traffic.txt).  They belong
 # to the default workloads with all heads; any other run reports null.
-MEASURED_TRAFFIC_BYTES = {"longvideo": 60.68e9 + 0.2839e9, "video": 0.4446e9 + 0.1085e9}
+MEASURED_TRAFFIC_BYTES = {"longvideo": 60.56e9 + 0.2839e9, "video": 0.4299e9 + 0.1085e9}
 
 
 CONFIGS_H = {"longvideo": 24, "video": 48}
