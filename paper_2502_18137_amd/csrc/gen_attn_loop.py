@@ -532,8 +532,8 @@ def gen_function(c, NST):
     return out
 
 
-def main():
-    here = os.path.dirname(os.path.abspath(__file__))
+def generate():
+    """The text of attn_loop_gfx950.inc."""
     out = ["// GENERATED by gen_attn_loop.py -- do not edit; edit the generator and run it again.",
            "// Steady-state iterations of the sparse flash loop as hand-scheduled gfx950 assembly.", ""]
     for D in (64, 128):
@@ -543,9 +543,15 @@ def main():
         for dt in ("f16", "bf16"):
             for NST in (2, 3):
                 out += gen_function(Cfg(D, dt, qk16=True), NST)
+    return "\n".join(out)
+
+
+def main():
+    here = os.path.dirname(os.path.abspath(__file__))
+    text = generate()
     with open(os.path.join(here, "attn_loop_gfx950.inc"), "w") as f:
-        f.write("\n".join(out))
-    print(f"wrote attn_loop_gfx950.inc ({len(out)} lines)")
+        f.write(text)
+    print(f"wrote attn_loop_gfx950.inc ({text.count(chr(10)) + 1} lines)")
 
 
 if __name__ == "__main__":
