@@ -34,13 +34,6 @@ Readings of the paper where it is silent or ambiguous (each also listed in the d
     maximum itself at every tile (the recurrence exactly as printed); ref_slack > 0 lets it lag:
     before a tile's softmax, if some row of a 32-row group has m - m_ref > ref_slack, the whole
     group's reference moves to the running maximum.  Only the rounding of P~ can tell the difference.
-  * Which P~ the row sum sees (Alg. 1 writes the same symbol in lines 13 and 16 and never rounds):
-    l_rounded = False sums P~ before it is rounded for the product (the default, used by every pin);
-    l_rounded = True sums the rounded values, i.e. the very P~ that multiplies V, so that every output
-    row is an exact convex combination of rows of V up to the product's own rounding.  The two differ
-    by the rounding error of l, about 2^-9 / sqrt(#keys that matter) relative for bf16.  The GPU kernels
-    follow the default (a dot-instruction row sum over the packed P~ was measured slower on gfx950: it
-    shares the matrix pipe).
   * FP8 P~V (the paper only credits a SageAttention2-based kernel with it, footnote of Sec. 1; no
     formulas): pv_dtype = "fp8e4m3".  V is quantized per (head, channel) over all tokens to OCP E4M3
     (1-4-3 bits, bias 7, subnormals, largest finite value 448, round to nearest even):
@@ -244,6 +237,46 @@ def _quant_blocks(X32: np.ndarray, b: int) -> Tuple[np.ndarray, np.ndarray]:
     return Xq, delta
 
 
+def quantize_exact(X32: np.ndarray, b: int) -> Tuple[np.ndarray, np.ndarray]:
+    """What Quant rounds to in exact arithmetic: x_hat = round-half-even(127 x / amax) per block, with no
+    intermediate rounding, and a flag for the elements whose quotient lies within 2^-15 of a half-integer.
+
+    Integer arithmetic throughout: an fp32 number is m * 2^e with a 24-bit integer m, so
+    127 x / amax = (127 m_x) / (m_a * 2^(e_a - e_x)) is a ratio of two integers that fit 64 bits whenever the
+    quotient is not negligibly small (below 2^-8 it rounds to 0 and is nowhere near a tie).
+    Outside the flag every sequence of correctly rounded fp32 operations whose relative error stays below
+    2^-22 -- in particular fl(x * fl(127/amax)), error < 2^-23 (1 + 2^-24), i.e. < 2^-16 absolute on a
+    quotient of at most 127 -- rounds to the same integer.  Returns (x_hat int8, near_tie bool)."""
+    assert X32.dtype == np.float32
+    N = X32.shape[0]
+    T = nblocks(N, b)
+    Xq = np.zeros(X32.shape, dtype=np.int8)
+    near = np.zeros(X32.shape, dtype=bool)
+    for t in range(T):
+        blk = X32[t * b:(t + 1) * b]
+        amax = np.float32(np.abs(blk).max())
+        if amax == 0:
+            continue
+        fm, fe = np.frexp(blk.astype(np.float64))             # x = fm * 2^fe, |fm| in [0.5, 1): exact
+        mx = np.rint(fm * 2.0 ** 24).astype(np.int64)          # 24-bit integer significand (signed)
+        ex = fe.astype(np.int64) - 24
+        am, ae = np.frexp(np.float64(amax))
+        ma, ea = int(round(am * 2.0 ** 24)), int(ae) - 24
+        sh = ea - ex                                            # >= 0 up to the significands' ratio
+        tiny = (sh > 33) | (mx == 0)                            # |127 x / amax| < 2^-8: rounds to 0, far from a tie
+        sh = np.where(tiny, 0, sh)
+        num = 127 * np.abs(mx)
+        num = np.where(sh < 0, num << np.maximum(-sh, 0), num)  # (sh = -1 can occur when m_x > m_a)
+        den = np.int64(ma) << np.maximum(sh, 0)
+        n = num // den
+        rem2 = 2 * (num - n * den)
+        up = (rem2 > den) | ((rem2 == den) & (n % 2 == 1))      # beyond the half, or a tie with n odd
+        mag = np.where(tiny, 0, n + up)
+        Xq[t * b:(t + 1) * b] = (np.sign(mx) * mag).astype(np.int8)
+        near[t * b:(t + 1) * b] = ~tiny & (np.abs(rem2 - den) < (den >> 14))   # |frac - 1/2| < 2^-15
+    return Xq, near
+
+
 def quantize_q(Q: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
     """Q-hat, delta_Q per 128-row block.  Q holds 16-bit values, taken exactly into fp32."""
     return _quant_blocks(np.asarray(Q, dtype=np.float32), BQ)
@@ -343,6 +376,10 @@ class AttnResult:
     valid_tiles: int         # tiles a full (causal) attention would need
     valid_groups: int        # row-group products of those tiles that have a visible (row, key) pair
     zero_rows: int           # rows that ended with l = 0 (must be 0 for a usable mask)
+    # per (Q block, row group): how close the stage-2 statistic max(m_local - m_ij) came to lambda over the
+    # row's tiles (inf when lambda = -inf or nothing was decided): a decision closer than the arithmetic of
+    # an implementation can resolve is not pinned, and the rows of that group inherit the doubt
+    lam_margin: Optional[np.ndarray] = None
 
     @property
     def sparsity(self) -> float:
@@ -353,8 +390,7 @@ class AttnResult:
 def sparse_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, mask: Optional[np.ndarray],
                      lam: float = -np.inf, scale: Optional[float] = None, causal: bool = False,
                      quant: bool = True, pv_dtype: str = "none",
-                     q_blocks: Optional[Sequence[int]] = None, ref_slack: float = 0.0,
-                     l_rounded: bool = False) -> AttnResult:
+                     q_blocks: Optional[Sequence[int]] = None, ref_slack: float = 0.0) -> AttnResult:
     """Algorithm 1's loop for one head.
 
     q_blocks: only these Q block indices i are processed (their rows of O and their share of the
@@ -367,7 +403,6 @@ def sparse_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, mask: Optional
     uses the unrounded P~.  mask=None means all ones.
     ref_slack (natural-log units): how far the running maximum may run ahead of the reference that
     exp subtracts (see the module header); 0 = the recurrence of Alg. 1 lines 12-16 as printed.
-    l_rounded: the row sum takes P~ after its rounding for the product (see the module header).
     """
     Q = np.asarray(Q, dtype=np.float64)
     K = np.asarray(K, dtype=np.float64)
@@ -387,6 +422,7 @@ def sparse_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, mask: Optional
         c_P = E4M3_MAX * math.exp(-ref_slack)
     O = np.zeros((N, d), dtype=np.float64)
     qk_tiles = pv_groups = valid_tiles = valid_groups = zero_rows = 0
+    lam_margin = np.full((Tm, BQ // ROW_GROUP), np.inf)
     for i in (range(Tm) if q_blocks is None else q_blocks):
         r0, r1 = i * BQ, min((i + 1) * BQ, N)
         nr = r1 - r0
@@ -435,11 +471,13 @@ def sparse_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, mask: Optional
             m_safe = np.where(live, m_ref, 0.0)
             P = np.exp(S - m_safe[:, None])          # exp(-inf) = 0 for masked entries
             Pr = round_e4m3(P * c_P) if fp8 else round16(P, pv_dtype)
-            l = l + ((Pr / c_P if fp8 else Pr) if l_rounded else P).sum(axis=1)
+            l = l + P.sum(axis=1)                    # line 13: the row sum sees the unrounded P~
             for g0 in range(0, nr, ROW_GROUP):
                 g1 = min(g0 + ROW_GROUP, nr)
                 with np.errstate(invalid="ignore"):
                     diff = np.where(m_local[g0:g1] > NEG_INF, m_local[g0:g1] - m_new[g0:g1], NEG_INF)
+                if np.isfinite(lam) and diff.max() > NEG_INF:
+                    lam_margin[i, g0 // ROW_GROUP] = min(lam_margin[i, g0 // ROW_GROUP], abs(diff.max() - lam))
                 if diff.max() > lam:
                     pv_groups += 1
                     Oi[g0:g1] = Oi[g0:g1] + Pr[g0:g1] @ V[c0:c1]
@@ -452,7 +490,7 @@ def sparse_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, mask: Optional
         if fp8:
             Oi = Oi * delta_V.astype(np.float64)[None, :] / c_P
         O[r0:r1] = np.where(dead[:, None], 0.0, Oi / np.where(dead, 1.0, l)[:, None])
-    return AttnResult(O, qk_tiles, pv_groups, valid_tiles, valid_groups, zero_rows)
+    return AttnResult(O, qk_tiles, pv_groups, valid_tiles, valid_groups, zero_rows, lam_margin)
 
 
 def dense_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, scale: Optional[float] = None,
@@ -496,12 +534,10 @@ def rel_l1(O: np.ndarray, O_ref: np.ndarray) -> float:
 
 def spargeattn(Q: np.ndarray, K: np.ndarray, V: np.ndarray, tau: float, theta: float, lam: float,
                causal: bool = False, scale: Optional[float] = None, quant: bool = True,
-               pv_dtype: str = "none", ref_slack: float = 0.0,
-               l_rounded: bool = False) -> Tuple[AttnResult, Prediction]:
+               pv_dtype: str = "none", ref_slack: float = 0.0) -> Tuple[AttnResult, Prediction]:
     """The whole of Algorithm 1 for one head: Quant, predict M_g, masked loop with the lambda skip."""
     pred = predict(Q, K, tau, theta, scale, causal)
-    res = sparse_attention(Q, K, V, pred.mask, lam, scale, causal, quant, pv_dtype, ref_slack=ref_slack,
-                           l_rounded=l_rounded)
+    res = sparse_attention(Q, K, V, pred.mask, lam, scale, causal, quant, pv_dtype, ref_slack=ref_slack)
     return res, pred
 
 
@@ -522,7 +558,7 @@ class TuneResult:
 def tune_head(inputs: Sequence[Tuple[np.ndarray, np.ndarray, np.ndarray]], tau_grid: Sequence[float],
               theta_grid: Sequence[float], lam_grid: Sequence[float], l1: float, l2: float,
               causal: bool = False, scale: Optional[float] = None, pv_dtype: str = "none",
-              ref_slack: float = 0.0, l_rounded: bool = False) -> TuneResult:
+              ref_slack: float = 0.0) -> TuneResult:
     """Sec. 3.6 for one attention head and a handful of inputs (Q, K, V).
 
     The error of a setting is L1 = sum|O - O'| / sum|O| with O the full attention computed the same way
@@ -539,13 +575,13 @@ def tune_head(inputs: Sequence[Tuple[np.ndarray, np.ndarray, np.ndarray]], tau_g
     def out(res):
         return round16(res.O, pv_dtype) if pv_dtype in ("fp16", "bf16") else res.O
 
-    refs = [out(sparse_attention(Q, K, V, None, -np.inf, scale, causal, True, pv_dtype, ref_slack=ref_slack,
-                                 l_rounded=l_rounded)) for (Q, K, V) in inputs]
+    refs = [out(sparse_attention(Q, K, V, None, -np.inf, scale, causal, True, pv_dtype, ref_slack=ref_slack))
+            for (Q, K, V) in inputs]
 
     def evaluate(tau, theta, lam):
         sp, err = [], []
         for (Q, K, V), ref in zip(inputs, refs):
-            res, _ = spargeattn(Q, K, V, tau, theta, lam, causal, scale, True, pv_dtype, ref_slack, l_rounded)
+            res, _ = spargeattn(Q, K, V, tau, theta, lam, causal, scale, True, pv_dtype, ref_slack)
             sp.append(res.sparsity)
             err.append(rel_l1(out(res), ref))
         return float(np.mean(sp)), float(np.max(err))

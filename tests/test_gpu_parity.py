@@ -1,8 +1,11 @@
 """GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
 
 Bars: INT8 values, scales, K mean and block masks bit-exact (mask entries the oracle flags as within
-1e-5 of a threshold are exempt); outputs within relative L1 2e-3 of the oracle that emulates the same
-quantization and P~ rounding, and within 3e-2 of exact fp64 attention restricted to the same blocks.
+1e-5 of a threshold are exempt; INT8 values also against the exactly rounded quotient away from ties);
+outputs, per head and per row, against three evaluations of Alg. 1 by the oracle -- P~ rounded where the
+kernel rounds it (relative L1 2e-3), the recurrence as printed with P~ rounded to 16 bits, and the loop
+with nothing rounded -- at the bars of tests/helpers.py, and within 3e-2 of exact fp64 attention
+restricted to the same blocks.
 """
 import math
 
@@ -12,7 +15,7 @@ import pytest
 from oracle import sparge_oracle as so
 from synth import CONFIGS
 from synth.workloads import scaled
-from tests.helpers import REF_SLACK, f32, gpu_inputs, small_workload, to_torch
+from tests.helpers import REF_SLACK, check_output_parity, f32, gpu_inputs, small_workload, to_torch
 
 pytestmark = pytest.mark.gpu
 
@@ -61,6 +64,13 @@ def test_quantize_bit_exact(sp, w):
         assert (km[0, h].view(np.uint32) == omean.view(np.uint32)).all()
         assert (Kq[0, h] == ok).all()
         assert (ks[0, h].view(np.uint32) == odk.view(np.uint32)).all()
+        # and against the mathematics: the exactly rounded quotient 127 x / amax wherever it is not within
+        # 2^-15 of a tie (there the fp32 sequence above is the specification)
+        qe, q_tie = so.quantize_exact(np.asarray(x["q"][0, h], dtype=np.float32), so.BQ)
+        ke, k_tie = so.quantize_exact(np.asarray(x["k"][0, h], dtype=np.float32) - omean[None, :], so.BK)
+        assert ((Qq[0, h] == qe) | q_tie).all() and ((Kq[0, h] == ke) | k_tie).all()
+        print(f"  head {h}: quotients within 2^-15 of a tie: Q {int(q_tie.sum())}, K {int(k_tie.sum())} of {q_tie.size}",
+              flush=True)
 
 
 @pytest.mark.parametrize("w", CASES, ids=IDS)
@@ -91,24 +101,23 @@ def test_predict_switches(sp, theta, tau):
 
 
 def check_attention(sp, w, x, Q, K, V, mask_np, lam, heads=None):
-    """GPU sparge_attn vs the oracle loop (emulated quantization) and vs exact fp64 on the same blocks."""
+    """GPU sparge_attn against the oracle loop on the same mask and lambda: the three evaluations and the bars
+    of helpers.check_output_parity (head level and per row), the counters, and, with the stage-2 test off,
+    exact fp64 attention on the same blocks."""
     import torch
     mask_t = None if mask_np is None else torch.from_numpy(mask_np).to("cuda")
     O, stats = sp.sparge_attn(Q, K, V, mask_t, lam, causal=w.causal, return_stats=True)
     O, stats = cpu(O).astype(np.float64), cpu(stats)
+    rows = np.arange(w.N)
     for h in (range(w.H) if heads is None else heads):
         q, k, v = x["q"][0, h], x["k"][0, h], x["v"][0, h]
         m = None if mask_np is None else mask_np[0, h]
-        ref = so.sparse_attention(q, k, v, m, lam=f32(lam), causal=w.causal, quant=True, pv_dtype=w.dtype,
-                                  ref_slack=REF_SLACK)
-        assert ref.zero_rows == 0
-        ref16 = so.round16(ref.O, w.dtype)
-        e_emul = so.rel_l1(O[0, h], ref16)
-        exact = so.dense_attention(q, k, v, causal=w.causal, block_mask=m)
-        e_exact = so.rel_l1(O[0, h], exact)
-        print(f"  head {h}: rel-L1 emul {e_emul:.2e} exact {e_exact:.2e} stats {stats[0, h].tolist()}", flush=True)
-        assert e_emul <= REL_L1_EMUL
+        res = check_output_parity(so, O[0, h], q, k, v, m, f32(lam), w.causal, w.dtype, rows,
+                                  label=f"{w.name} head {h} lambda {lam}")
+        ref = res["ref"]
         if not np.isfinite(lam):
+            e_exact = so.rel_l1(O[0, h], so.dense_attention(q, k, v, causal=w.causal, block_mask=m))
+            print(f"    exact fp64 on the same blocks: {e_exact:.2e}; stats {stats[0, h].tolist()}", flush=True)
             assert e_exact <= REL_L1_EXACT
         assert stats[0, h, 0] == ref.qk_tiles
         assert stats[0, h, 2] == ref.valid_tiles and stats[0, h, 3] == ref.valid_groups

@@ -9,7 +9,7 @@ import numpy as np
 import pytest
 
 from oracle import sparge_oracle as so
-from tests.helpers import REF_SLACK, f32, gpu_inputs, small_workload
+from tests.helpers import REF_SLACK, check_output_parity, f32, gpu_inputs, small_workload
 
 pytestmark = pytest.mark.gpu
 
@@ -64,5 +64,8 @@ def test_random_problem(sp, seed):
     err = so.rel_l1(O, so.round16(ref.O, dtype))
     print(f"  rel-L1 {err:.2e}; tiles {stats[0]}/{stats[2]}, row groups {stats[1]}/{stats[3]}", flush=True)
     assert err <= 2e-3
+    if variant == "int8":
+        check_output_parity(so, O, x["q"][0, 0], x["k"][0, 0], x["v"][0, 0], mask[0, 0], f32(lam), causal, dtype,
+                            np.arange(N), label=f"seed {seed}")
     assert stats[0] == ref.qk_tiles and stats[2] == ref.valid_tiles and stats[3] == ref.valid_groups
     assert abs(int(stats[1]) - ref.pv_groups) <= max(2, ref.pv_groups // 200)

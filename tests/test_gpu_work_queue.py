@@ -10,7 +10,7 @@ import numpy as np
 import pytest
 
 from oracle import sparge_oracle as so
-from tests.helpers import REF_SLACK, f32, gpu_inputs, small_workload
+from tests.helpers import REF_SLACK, check_output_parity, f32, gpu_inputs, small_workload
 
 pytestmark = pytest.mark.gpu
 
@@ -60,6 +60,9 @@ def test_unbalanced_heads(sp, H, N, d, causal, dense_heads):
         rows = np.arange(N) if qb is None else np.concatenate([np.arange(128 * i, min(128 * (i + 1), N)) for i in qb])
         err = so.rel_l1(O[h][rows], so.round16(ref.O[rows], "bf16"))
         assert err <= 2e-3, (h, err)
+        if h in full:
+            check_output_parity(so, O[h][rows], x["q"][0, h], x["k"][0, h], x["v"][0, h], mask[0, h], f32(lam), causal,
+                                "bf16", rows, q_blocks=qb, label=f"H={H} N={N} head {h}")
         if qb is None:
             assert stats[h][0] == ref.qk_tiles and stats[h][2] == ref.valid_tiles
     # the counters of every head: executed tiles = kept blocks of its mask (causal: the visible ones)
