@@ -5,10 +5,18 @@
  *
  * General rules for every entry point
  *   - Every data pointer is DEVICE memory owned by the caller unless marked "host".  The library
- *     never allocates, never frees, keeps no pointer after returning and holds no global state
- *     besides a thread-local error string (and the optional timing events, see the end).
- *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = default
- *     stream).  No entry point synchronises the host; results are valid after the stream reaches
+ *     allocates and frees no device memory and keeps no pointer after returning; intermediates live in the
+ *     workspace `ws` the caller passes (sparge_workspace_bytes; 256-byte aligned).  A workspace carries no
+ *     state between calls, but two calls that may run at the same time (different streams, replays of
+ *     different graphs) must not share one: besides intermediates it holds the item counters of the
+ *     attention kernel's work distribution.
+ *   - What the library does own, per process: a thread-local error string and the thread-local timing-event
+ *     arrays of sparge_set_timing_events; the compute-unit count of each device, looked up at the first
+ *     attention launch there; and, for sparge_forward only, one extra HIP stream and two events per device,
+ *     created at the first sparge_forward on that device and never destroyed (see there for what that
+ *     means for stream capture and host threads).  sparge_tune uses host memory for its tables.
+ *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = default stream).  No
+ *     entry point except sparge_tune synchronises the host; results are valid after the stream reaches
  *     the end of the enqueued work.
  *   - Return value: SPARGE_OK or a negative error code; sparge_last_error() then describes it.
  *     Invalid arguments are rejected before anything is enqueued.
@@ -51,7 +59,7 @@ enum { SPARGE_QK_INT8 = 0, SPARGE_QK_16BIT = 1 };
 
 /* which entry point a workspace is sized for */
 enum { SPARGE_WS_QUANTIZE = 0, SPARGE_WS_PREDICT = 1, SPARGE_WS_ATTN = 2, SPARGE_WS_ATTN_QUANTIZED = 3,
-       SPARGE_WS_FORWARD = 4 };
+       SPARGE_WS_FORWARD = 4, SPARGE_WS_ATTN_TILED = 5 };
 
 typedef struct sparge_desc {
     int32_t B, H, N, d;
@@ -68,7 +76,8 @@ const char* sparge_last_error(void);
 int sparge_version(void);
 
 /* Bytes of device scratch `ws` the given entry point (SPARGE_WS_*) needs for this shape.
- * The workspace needs 256-byte alignment and carries no state between calls. */
+ * The workspace needs 256-byte alignment and carries no state between calls; calls that may overlap in
+ * time need one each. */
 int sparge_workspace_bytes(const sparge_desc* desc, int entry, size_t* bytes /* host, out */);
 
 /*
@@ -120,9 +129,8 @@ int sparge_predict(const void* Q, const void* K, const sparge_desc* desc,
  * P~V row-group products executed, tiles a full attention needs, row-group products a full
  * attention needs}; it is overwritten, not accumulated.
  * Work distribution: the launch is two resident workgroups per compute unit that take (head, Q block)
- * items from counters in a static device array of the library (64 sets, one per launch in rotation,
- * cleared by a one-wave kernel enqueued in front of the launch).  More than 64 attention launches in
- * flight at once on one device (other streams) would share a set; results are undefined then.
+ * items from eight counters (one per XCD range of items) kept in `ws` and cleared by a one-wave kernel
+ * enqueued in front of the launch; which workgroup computes an item depends on timing, the result does not.
  */
 int sparge_attn_quantized(const int8_t* Qq, const int8_t* Kq, const float* q_scale, const float* k_scale,
                           const void* V, const sparge_desc* desc, const uint8_t* mask,
@@ -145,14 +153,15 @@ int sparge_attn_quantized(const int8_t* Qq, const int8_t* Kq, const float* q_sca
  *   Output: E4M3 bytes [B,H,T_n,d/32,2,64,16]: (channel tile, key half h2, lane = c%32 + 32 g, byte b)
  *   holds channel c of key 64 j + 32 h2 + 8 (b/4) + 4 g + b%4 (keys >= N are 0); then, 256-byte
  *   aligned, delta_V fp32 [B,H,d]; then, 256-byte aligned, the fp32 bit patterns of the channel maxima.
- * sparge_attn_tiled is sparge_attn_quantized with V already in that form; it needs no workspace.
+ * sparge_attn_tiled is sparge_attn_quantized with V already in that form; its workspace
+ * (SPARGE_WS_ATTN_TILED, 1 KB) holds the item counters only.
  */
 int sparge_v_tiles_bytes(const sparge_desc* desc, size_t* bytes /* host, out */);
 int sparge_v_tiles(const void* V, const sparge_desc* desc, void* v_tiles, void* hip_stream);
 int sparge_attn_tiled(const int8_t* Qq, const int8_t* Kq, const float* q_scale, const float* k_scale,
                       const void* v_tiles, const sparge_desc* desc, const uint8_t* mask,
                       const float* lambda, float sm_scale, int causal,
-                      void* O, uint64_t* stats, void* hip_stream);
+                      void* O, uint64_t* stats, void* ws, size_t ws_bytes, void* hip_stream);
 
 /* Same as sparge_quantize followed by sparge_attn_quantized, with Q-hat/K-hat kept in `ws`. */
 int sparge_attn(const void* Q, const void* K, const void* V, const sparge_desc* desc,
@@ -167,9 +176,12 @@ int sparge_attn(const void* Q, const void* K, const void* V, const sparge_desc* 
  * keeps per device (created at the first call on that device, default priority, never destroyed),
  * forked from `hip_stream` after the block statistics and joined to it before the attention kernel,
  * next to the block predictor on `hip_stream`.  For the caller the call is ordered on `hip_stream`
- * like any other; a stream capture of `hip_stream` takes the second stream in and releases it at
- * the join (make the first call on a device outside a capture).  Calls from several host threads
- * share that stream and enqueue one after the other.
+ * like any other.  A stream capture of `hip_stream` takes the second stream into the capture at the fork
+ * and releases it at the join, inside this call; make the first call on a device outside a capture (the
+ * stream cannot be created inside one).  Host threads: calls are serialised by a mutex while they
+ * enqueue and share the second stream, so their side passes run one after the other.  Graphs captured
+ * from this call hold no reference to that stream and may be replayed concurrently on different
+ * streams, each with its own workspace, outputs and mask.
  */
 int sparge_forward(const void* Q, const void* K, const void* V, const sparge_desc* desc,
                    const float* tau, const float* theta, const float* lambda,
@@ -179,7 +191,8 @@ int sparge_forward(const void* Q, const void* K, const void* V, const sparge_des
 /*
  * Relative L1 distance of Sec. 3.6, L1 = sum|O - O'| / sum|O| with O the reference: per (batch, head)
  * the two sums.  O, O_ref: 16-bit tensors laid out as desc says; out: device fp64 [B,H,2] =
- * {sum|O_ref - O|, sum|O_ref|}, overwritten.
+ * {sum|O_ref - O|, sum|O_ref|}, overwritten.  The summation order is fixed (one workgroup per (batch, head)):
+ * the same inputs give the same bits on every call.
  */
 int sparge_rel_l1(const void* O, const void* O_ref, const sparge_desc* desc, double* out /* device */,
                   void* hip_stream);

@@ -24,5 +24,5 @@ from .binding import (  # noqa: F401
     tensor_from_numpy,
     REF_SLACK_LOG2,
     REF_SLACK_LOG2_FP8,
-    WS_ATTN, WS_ATTN_QUANTIZED, WS_FORWARD, WS_PREDICT, WS_QUANTIZE,
+    WS_ATTN, WS_ATTN_QUANTIZED, WS_ATTN_TILED, WS_FORWARD, WS_PREDICT, WS_QUANTIZE,
 )

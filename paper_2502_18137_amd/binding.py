@@ -13,7 +13,7 @@ from typing import Optional, Sequence, Tuple, Union
 
 import torch
 
-WS_QUANTIZE, WS_PREDICT, WS_ATTN, WS_ATTN_QUANTIZED, WS_FORWARD = range(5)
+WS_QUANTIZE, WS_PREDICT, WS_ATTN, WS_ATTN_QUANTIZED, WS_FORWARD, WS_ATTN_TILED = range(6)
 BQ, BK = 128, 64
 REF_SLACK_LOG2 = 8      # SPARGE_REF_SLACK_LOG2 of sparge.h
 REF_SLACK_LOG2_FP8 = 2  # SPARGE_REF_SLACK_LOG2_FP8
@@ -59,7 +59,8 @@ def load_library() -> ctypes.CDLL:
                                           vp, ctypes.c_size_t, vp]
     lib.sparge_v_tiles.argtypes = [vp, dp, vp, vp]
     lib.sparge_v_tiles_bytes.argtypes = [dp, ctypes.POINTER(ctypes.c_size_t)]
-    lib.sparge_attn_tiled.argtypes = [vp, vp, vp, vp, vp, dp, vp, f32p, ctypes.c_float, ctypes.c_int, vp, vp, vp]
+    lib.sparge_attn_tiled.argtypes = [vp, vp, vp, vp, vp, dp, vp, f32p, ctypes.c_float, ctypes.c_int, vp, vp, vp,
+                                      ctypes.c_size_t, vp]
     f64p = ctypes.POINTER(ctypes.c_double)
     lib.sparge_rel_l1.argtypes = [vp, vp, dp, vp, vp]
     lib.sparge_tune_workspace_bytes.argtypes = [dp, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t)]
@@ -235,7 +236,7 @@ def sparge_v_tiles(V: torch.Tensor, pv_fp8: bool = False) -> torch.Tensor:
 def sparge_attn_tiled(Qq, Kq, q_scale, k_scale, v_tiles: torch.Tensor, like: torch.Tensor,
                       mask: Optional[torch.Tensor], lam, causal: bool = False, sm_scale: float = 0.0,
                       stats: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
-                      pv_fp8: bool = False):
+                      pv_fp8: bool = False, ws: Optional[torch.Tensor] = None):
     """The sparse flash loop alone.  `like` gives O's shape/strides/dtype (the V it was tiled from)."""
     d = _desc(like, pv_fp8)
     B, H, N, dim = like.shape
@@ -249,9 +250,10 @@ def sparge_attn_tiled(Qq, Kq, q_scale, k_scale, v_tiles: torch.Tensor, like: tor
         raise SpargeError("v_tiles must come from sparge_v_tiles for this shape and pv_fp8 setting")
     O = torch.empty_like(like) if out is None else out
     _same_layout(like, O)
+    ws = _workspace(like, WS_ATTN_TILED, ws, pv_fp8)
     _check(load_library().sparge_attn_tiled(_ptr(Qq), _ptr(Kq), _ptr(q_scale), _ptr(k_scale), _ptr(v_tiles),
                                             ctypes.byref(d), _ptr(mask), _per_head(lam, H), float(sm_scale),
-                                            int(causal), _ptr(O), _ptr(stats), _stream()))
+                                            int(causal), _ptr(O), _ptr(stats), _ptr(ws), ws.numel(), _stream()))
     return O
 
 

@@ -1,6 +1,7 @@
 // C ABI of libsparge: argument validation, workspace partition, kernel sequencing.
-// Nothing here allocates device memory or synchronises; every kernel goes onto the caller's stream, except
-// that sparge_forward runs three passes on a second stream between a fork and a join on the caller's.
+// Nothing here allocates device memory; every kernel goes onto the caller's stream, except that
+// sparge_forward runs three passes on a second stream between a fork and a join on the caller's.  Only
+// sparge_tune synchronises (it decides on the host between candidates).
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -93,7 +94,7 @@ bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) !
 
 // Partition of the scratch buffer.  Every entry point uses a subset; offsets are fixed by shape.
 struct Workspace {
-    size_t pooled_q, ksum_t, sim_q, sim_k, k_mean, logits, Qq, Kq, q_scale, k_scale, v_tiles, mask, total;
+    size_t pooled_q, ksum_t, sim_q, sim_k, k_mean, logits, Qq, Kq, q_scale, k_scale, v_tiles, mask, queue, total;
 };
 
 Workspace plan(const Shape& s, int entry) {
@@ -103,6 +104,7 @@ Workspace plan(const Shape& s, int entry) {
     const bool pred = entry == SPARGE_WS_PREDICT || entry == SPARGE_WS_FORWARD;
     const bool quant_in_ws = entry == SPARGE_WS_ATTN || entry == SPARGE_WS_FORWARD;
     const bool attn = entry == SPARGE_WS_ATTN || entry == SPARGE_WS_ATTN_QUANTIZED || entry == SPARGE_WS_FORWARD;
+    const bool loop = attn || entry == SPARGE_WS_ATTN_TILED;
     Workspace w{};
     size_t off = 0;
     auto take = [&](bool used, size_t bytes) { size_t o = off; if (used) off += align256(bytes); return o; };
@@ -118,6 +120,7 @@ Workspace plan(const Shape& s, int entry) {
     w.k_scale = take(quant_in_ws, BH * s.Tn * sizeof(float));
     w.v_tiles = take(attn, v_tiles_layout(s).total);
     w.mask = take(entry == SPARGE_WS_FORWARD, BH * s.Tm * s.Tn);
+    w.queue = take(loop, ATTN_QUEUE_BYTES);  // item counters of the attention kernel's work distribution
     w.total = off ? off : 256;
     return w;
 }
@@ -219,7 +222,7 @@ int run_predict(const Shape& s, void* ws, const Workspace& w, const HeadParams& 
 // The attention launch, bracketed by the caller's timing events when some are installed.
 int timed_attn(const void* Qq, const void* Kq, const float* q_scale, const float* k_scale,
                const void* v_tiles, const Shape& s, const uint8_t* mask, const HeadParams& lam, float sm_scale,
-               int causal, void* O, uint64_t* stats, hipStream_t st) {
+               int causal, void* O, uint64_t* stats, unsigned int* queue, hipStream_t st) {
     const bool timed = g_ev_start && g_ev_k < g_ev_n;
     hipError_t e;
     if (stats && (e = launch_zero_stats(reinterpret_cast<unsigned long long*>(stats), s.B * s.H * 4, st)) != hipSuccess)
@@ -227,7 +230,7 @@ int timed_attn(const void* Qq, const void* Kq, const float* q_scale, const float
     if (timed && (e = hipEventRecord(static_cast<hipEvent_t>(g_ev_start[g_ev_k]), st)) != hipSuccess)
         return hip_fail(e, "record start event");
     if ((e = launch_attn(Qq, Kq, q_scale, k_scale, v_tiles, v_scale_of(v_tiles, s), s, mask, lam, sm_scale, causal, O,
-                         reinterpret_cast<unsigned long long*>(stats), st)) != hipSuccess)
+                         reinterpret_cast<unsigned long long*>(stats), queue, st)) != hipSuccess)
         return hip_fail(e, "attn");
     if (timed) {
         if ((e = hipEventRecord(static_cast<hipEvent_t>(g_ev_stop[g_ev_k]), st)) != hipSuccess)
@@ -239,10 +242,10 @@ int timed_attn(const void* Qq, const void* Kq, const float* q_scale, const float
 
 int run_attn(const void* Qq, const void* Kq, const float* q_scale, const float* k_scale, const void* V,
              const Shape& s, void* v_tiles, const uint8_t* mask, const HeadParams& lam, float sm_scale,
-             int causal, void* O, uint64_t* stats, hipStream_t st) {
+             int causal, void* O, uint64_t* stats, unsigned int* queue, hipStream_t st) {
     hipError_t e;
     if ((e = retile_v(V, s, v_tiles, st)) != hipSuccess) return hip_fail(e, "v_tiles");
-    return timed_attn(Qq, Kq, q_scale, k_scale, v_tiles, s, mask, lam, sm_scale, causal, O, stats, st);
+    return timed_attn(Qq, Kq, q_scale, k_scale, v_tiles, s, mask, lam, sm_scale, causal, O, stats, queue, st);
 }
 
 }  // namespace
@@ -258,7 +261,7 @@ int sparge_workspace_bytes(const sparge_desc* desc, int entry, size_t* bytes) {
     int rc = check_desc(desc, &s);
     if (rc) return rc;
     if (!bytes) return fail(SPARGE_EINVAL, "bytes is NULL");
-    if (entry < SPARGE_WS_QUANTIZE || entry > SPARGE_WS_FORWARD) return fail(SPARGE_EINVAL, "unknown entry %d", entry);
+    if (entry < SPARGE_WS_QUANTIZE || entry > SPARGE_WS_ATTN_TILED) return fail(SPARGE_EINVAL, "unknown entry %d", entry);
     *bytes = plan(s, entry).total;
     return SPARGE_OK;
 }
@@ -319,7 +322,7 @@ int sparge_attn_quantized(const int8_t* Qq, const int8_t* Kq, const float* q_sca
     const Workspace w = plan(s, SPARGE_WS_ATTN_QUANTIZED);
     if ((rc = check_ws(w, ws, ws_bytes))) return rc;
     return run_attn(Qq, Kq, q_scale, k_scale, V, s, at<char>(ws, w.v_tiles), mask, lam, sm_scale, causal, O,
-                    stats, static_cast<hipStream_t>(hip_stream));
+                    stats, at<unsigned int>(ws, w.queue), static_cast<hipStream_t>(hip_stream));
 }
 
 int sparge_v_tiles_bytes(const sparge_desc* desc, size_t* bytes) {
@@ -343,7 +346,8 @@ int sparge_v_tiles(const void* V, const sparge_desc* desc, void* v_tiles, void* 
 
 int sparge_attn_tiled(const int8_t* Qq, const int8_t* Kq, const float* q_scale, const float* k_scale,
                       const void* v_tiles, const sparge_desc* desc, const uint8_t* mask, const float* lambda,
-                      float sm_scale, int causal, void* O, uint64_t* stats, void* hip_stream) {
+                      float sm_scale, int causal, void* O, uint64_t* stats, void* ws, size_t ws_bytes,
+                      void* hip_stream) {
     Shape s;
     int rc = check_desc(desc, &s);
     if (rc) return rc;
@@ -352,8 +356,10 @@ int sparge_attn_tiled(const int8_t* Qq, const int8_t* Kq, const float* q_scale, 
         return fail(SPARGE_EINVAL, "tensor pointers must be 16-byte aligned");
     HeadParams lam;
     if ((rc = check_lambda(lambda, s.H, &lam))) return rc;
+    const Workspace w = plan(s, SPARGE_WS_ATTN_TILED);
+    if ((rc = check_ws(w, ws, ws_bytes))) return rc;
     return timed_attn(Qq, Kq, q_scale, k_scale, v_tiles, s, mask, lam, sm_scale, causal,
-                      O, stats, static_cast<hipStream_t>(hip_stream));
+                      O, stats, at<unsigned int>(ws, w.queue), static_cast<hipStream_t>(hip_stream));
 }
 
 int sparge_attn(const void* Q, const void* K, const void* V, const sparge_desc* desc, const uint8_t* mask,
@@ -371,13 +377,14 @@ int sparge_attn(const void* Q, const void* K, const void* V, const sparge_desc* 
     if ((rc = check_ws(w, ws, ws_bytes))) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (s.qk16)  // the products run on Q and K as they are: nothing to quantize
-        return run_attn(Q, K, nullptr, nullptr, V, s, at<char>(ws, w.v_tiles), mask, lam, sm_scale, causal, O, stats, st);
+        return run_attn(Q, K, nullptr, nullptr, V, s, at<char>(ws, w.v_tiles), mask, lam, sm_scale, causal, O, stats,
+                        at<unsigned int>(ws, w.queue), st);
     if ((rc = run_stats_and_quant(Q, K, s, at<double>(ws, w.pooled_q), at<double>(ws, w.ksum_t),
                                   at<double>(ws, w.sim_q), at<double>(ws, w.sim_k), at<int8_t>(ws, w.Qq),
                                   at<float>(ws, w.q_scale), at<int8_t>(ws, w.Kq), at<float>(ws, w.k_scale),
                                   at<float>(ws, w.k_mean), st))) return rc;
     return run_attn(at<int8_t>(ws, w.Qq), at<int8_t>(ws, w.Kq), at<float>(ws, w.q_scale), at<float>(ws, w.k_scale),
-                    V, s, at<char>(ws, w.v_tiles), mask, lam, sm_scale, causal, O, stats, st);
+                    V, s, at<char>(ws, w.v_tiles), mask, lam, sm_scale, causal, O, stats, at<unsigned int>(ws, w.queue), st);
 }
 
 int sparge_forward(const void* Q, const void* K, const void* V, const sparge_desc* desc, const float* tau,
@@ -409,7 +416,8 @@ int sparge_forward(const void* Q, const void* K, const void* V, const sparge_des
                                       q8 ? at<float>(ws, w.q_scale) : nullptr, q8 ? at<int8_t>(ws, w.Kq) : nullptr,
                                       at<float>(ws, w.k_scale), at<float>(ws, w.k_mean), st))) return rc;
         if ((rc = run_predict(s, ws, w, t, th, sm_scale, causal, mask, st))) return rc;
-        return run_attn(Qa, Ka, qsc, ksc, V, s, at<char>(ws, w.v_tiles), mask, lam, sm_scale, causal, O, stats, st);
+        return run_attn(Qa, Ka, qsc, ksc, V, s, at<char>(ws, w.v_tiles), mask, lam, sm_scale, causal, O, stats,
+                        at<unsigned int>(ws, w.queue), st);
     }
     // caller's stream: block statistics (+ Q quantization) -> fork -> predictor -> join -> attention
     // second stream:                                  fork -> V tiles, K mean, K quantization -> join
@@ -437,7 +445,8 @@ int sparge_forward(const void* Q, const void* K, const void* V, const sparge_des
     if ((e = hipStreamWaitEvent(st, side->join, 0)) != hipSuccess) return hip_fail(e, "wait join");
     if (rc_side) return rc_side;
     if (rc) return rc;
-    return timed_attn(Qa, Ka, qsc, ksc, at<char>(ws, w.v_tiles), s, mask, lam, sm_scale, causal, O, stats, st);
+    return timed_attn(Qa, Ka, qsc, ksc, at<char>(ws, w.v_tiles), s, mask, lam, sm_scale, causal, O, stats,
+                      at<unsigned int>(ws, w.queue), st);
 }
 
 int sparge_rel_l1(const void* O, const void* O_ref, const sparge_desc* desc, double* out, void* hip_stream) {
@@ -529,7 +538,8 @@ int sparge_tune(const void* const* Q, const void* const* K, const void* const* V
                                       at<float>(f, w.q_scale), at<int8_t>(f, w.Kq), at<float>(f, w.k_scale),
                                       at<float>(f, w.k_mean), st))) return rc;
         if ((rc = run_attn(at<int8_t>(f, w.Qq), at<int8_t>(f, w.Kq), at<float>(f, w.q_scale), at<float>(f, w.k_scale),
-                           V[n], s, at<char>(f, w.v_tiles), nullptr, off, sm_scale, causal, o_ref(n), nullptr, st)))
+                           V[n], s, at<char>(f, w.v_tiles), nullptr, off, sm_scale, causal, o_ref(n), nullptr,
+                           at<unsigned int>(f, w.queue), st)))
             return rc;
     }
 
@@ -544,7 +554,7 @@ int sparge_tune(const void* const* Q, const void* const* K, const void* const* V
             if ((r = run_predict(s, f, w, tp, thp, sm_scale, causal, at<uint8_t>(f, w.mask), st))) return r;
             if ((r = timed_attn(at<int8_t>(f, w.Qq), at<int8_t>(f, w.Kq), at<float>(f, w.q_scale),
                                 at<float>(f, w.k_scale), at<char>(f, w.v_tiles), s, at<uint8_t>(f, w.mask), lp,
-                                sm_scale, causal, o_cur, d_stats, st))) return r;
+                                sm_scale, causal, o_cur, d_stats, at<unsigned int>(f, w.queue), st))) return r;
             if ((e = launch_rel_l1(o_cur, o_ref(n), s, d_metrics, st)) != hipSuccess) return hip_fail(e, "rel_l1");
             if ((e = hipMemcpyAsync(h_metrics.data(), d_metrics, BH * 2 * sizeof(double), hipMemcpyDeviceToHost, st)) != hipSuccess)
                 return hip_fail(e, "copy error sums");

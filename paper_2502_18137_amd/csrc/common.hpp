@@ -102,17 +102,20 @@ hipError_t launch_topcdf(const double* logits, const double* sim_q, const double
 hipError_t launch_v_tiles(const void* V, const Shape& s, uint16_t* v_tiles, hipStream_t st);
 // stats[0..n) = 0 (a fill kernel, not a memset node, so callers may capture it in a graph).
 hipError_t launch_zero_stats(unsigned long long* stats, int n, hipStream_t st);
-// The sparse flash loop (accumulates into stats).
+// The sparse flash loop (accumulates into stats).  queue: ATTN_QUEUE_BYTES of device memory for the item
+// counters of the work distribution, cleared here by a fill kernel in front of the launch; it must not be
+// shared with another launch that may run at the same time.
+constexpr size_t ATTN_QUEUE_BYTES = 1024;
 hipError_t launch_attn(const void* Qp, const void* Kp, const float* q_scale, const float* k_scale,
                        const void* v_tiles, const float* v_scale, const Shape& s, const uint8_t* mask,
                        const HeadParams& lambda, float sm_scale, int causal, void* O, unsigned long long* stats,
-                       hipStream_t st);
+                       unsigned int* queue, hipStream_t st);
 // FP8 form of V: per-(b,h,channel) |V| maxima (as fp32 bit patterns, zeroed here), scales amax/448, and
 // E4M3 tiles in the operand order of the 32x32x64 MFMA.
 hipError_t launch_v_tiles_fp8(const void* V, const Shape& s, unsigned char* tiles, float* v_scale,
                               uint32_t* amax_bits, hipStream_t st);
 
-// out[b,h] = {sum|Oref - O|, sum|Oref|} in fp64 (zeroed here), both tensors laid out as the shape says.
+// out[b,h] = {sum|Oref - O|, sum|Oref|} in fp64 (overwritten; fixed summation order), both tensors laid out as the shape says.
 hipError_t launch_rel_l1(const void* O, const void* Oref, const Shape& s, double* out, hipStream_t st);
 
 // Order in which a Hilbert curve visits the row-major cells of a T x H x W grid (host; perm has T*H*W entries).

@@ -6,24 +6,19 @@ namespace sparge {
 
 namespace {
 
-__global__ void zero_f64_kernel(double* p, int n) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0.0;
-}
-
-constexpr int L1_ROWS = 256;  // tokens per workgroup
-
+// One workgroup of 1024 threads per (batch, head): every thread sums a fixed set of elements in a fixed
+// order and the partial sums are combined by a fixed tree, so the result does not depend on scheduling
+// (the hyper-parameter search compares these sums with its bounds: it must decide the same way every time).
 template <int D, int DT>
-__global__ __launch_bounds__(256) void rel_l1_kernel(const uint16_t* __restrict__ O, const uint16_t* __restrict__ Oref,
-                                                     Shape s, double* __restrict__ out) {
-    constexpr int CPR = D / 8, RPI = 256 / CPR;
-    __shared__ double red[2][256];
-    const int h = blockIdx.y, b = blockIdx.z;
+__global__ __launch_bounds__(1024) void rel_l1_kernel(const uint16_t* __restrict__ O, const uint16_t* __restrict__ Oref,
+                                                      Shape s, double* __restrict__ out) {
+    constexpr int CPR = D / 8, RPI = 1024 / CPR;
+    __shared__ double red[2][1024];
+    const int h = blockIdx.x, b = blockIdx.y;
     const long long base = b * s.sb + h * s.sh;
     const int col = threadIdx.x % CPR, r0 = threadIdx.x / CPR;
-    const int row_begin = blockIdx.x * L1_ROWS, row_end = min(row_begin + L1_ROWS, s.N);
     double num = 0.0, den = 0.0;
-    for (int row = row_begin + r0; row < row_end; row += RPI) {
+    for (int row = r0; row < s.N; row += RPI) {
         const long long off = base + (long long)row * s.sn + col * 8;
         const uint4 a = *reinterpret_cast<const uint4*>(O + off);
         const uint4 r = *reinterpret_cast<const uint4*>(Oref + off);
@@ -42,7 +37,7 @@ __global__ __launch_bounds__(256) void rel_l1_kernel(const uint16_t* __restrict_
     red[0][threadIdx.x] = num;
     red[1][threadIdx.x] = den;
     __syncthreads();
-    for (int st = 128; st > 0; st >>= 1) {
+    for (int st = 512; st > 0; st >>= 1) {
         if (threadIdx.x < st) {
             red[0][threadIdx.x] += red[0][threadIdx.x + st];
             red[1][threadIdx.x] += red[1][threadIdx.x + st];
@@ -51,20 +46,18 @@ __global__ __launch_bounds__(256) void rel_l1_kernel(const uint16_t* __restrict_
     }
     if (threadIdx.x == 0) {
         const long long bh = (long long)b * s.H + h;
-        atomicAdd(&out[bh * 2 + 0], red[0][0]);
-        atomicAdd(&out[bh * 2 + 1], red[1][0]);
+        out[bh * 2 + 0] = red[0][0];
+        out[bh * 2 + 1] = red[1][0];
     }
 }
 
 }  // namespace
 
 hipError_t launch_rel_l1(const void* O, const void* Oref, const Shape& s, double* out, hipStream_t st) {
-    const int n = s.B * s.H * 2;
-    hipLaunchKernelGGL(zero_f64_kernel, dim3((n + 255) / 256), dim3(256), 0, st, out, n);
-    dim3 grid((s.N + L1_ROWS - 1) / L1_ROWS, s.H, s.B);
+    dim3 grid(s.H, s.B);
     const uint16_t* a = static_cast<const uint16_t*>(O);
     const uint16_t* r = static_cast<const uint16_t*>(Oref);
-#define CALL(D, DT) hipLaunchKernelGGL((rel_l1_kernel<D, DT>), grid, dim3(256), 0, st, a, r, s, out);
+#define CALL(D, DT) hipLaunchKernelGGL((rel_l1_kernel<D, DT>), grid, dim3(1024), 0, st, a, r, s, out);
     if (s.d == 64 && s.dtype == SPARGE_F16) CALL(64, SPARGE_F16)
     else if (s.d == 64 && s.dtype == SPARGE_BF16) CALL(64, SPARGE_BF16)
     else if (s.d == 128 && s.dtype == SPARGE_F16) CALL(128, SPARGE_F16)

@@ -451,6 +451,10 @@ hipError_t launch_topcdf(const double* logits, const double* sim_q, const double
     int npad = 2;
     while (npad < s.Tn) npad <<= 1;
     const size_t smem = static_cast<size_t>(npad) * (sizeof(double) + sizeof(unsigned long long) + 1);
+    // 68 KB at the longest rows: more than the 64 KB a launch gets without asking (the CU has 160 KB)
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(topcdf_kernel),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(smem));
+    if (e != hipSuccess) return e;
     dim3 grid(s.Tm, s.H, s.B);
     hipLaunchKernelGGL(topcdf_kernel, grid, dim3(256), smem, st, logits, sim_q, sim_k, s, tau, theta, causal,
                        npad, mask);

@@ -53,3 +53,44 @@ def test_forward_replays_from_a_graph(sp, variant):
         junk = (torch.randn(1 << 20, device="cuda") * 2).sum()   # unrelated eager work between replays
         torch.cuda.synchronize()
         assert torch.isfinite(junk)
+
+
+def test_two_graphs_replayed_on_two_streams(sp):
+    """Two captures of sparge_forward, each with its own workspace, outputs and inputs (one causal), replayed at
+    the same time on two streams, three rounds with eager launches in between: every replay reproduces its
+    eager result bit for bit.  (The item counters of the attention kernel live in each call's workspace: two
+    launches in flight share nothing.)"""
+    import torch
+    cases = []
+    for seed, causal, d in ((21, False, 128), (22, True, 64)):
+        w = small_workload(f"g{seed}", N=4000, d=d, dtype="bf16", H=6, seed=seed, causal=causal)
+        x, Q, K, V = gpu_inputs(w)
+        eager, mask, stats = sp.sparge_forward(Q, K, V, w.tau, w.theta, w.lam, causal=causal, return_mask=True,
+                                               return_stats=True)
+        ws = torch.empty(sp.sparge_workspace_bytes(Q, sp.WS_FORWARD), dtype=torch.uint8, device="cuda")
+        O = torch.empty_like(V)
+        st = torch.cuda.Stream()
+        g = torch.cuda.CUDAGraph()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(st):
+            sp.sparge_forward(Q, K, V, w.tau, w.theta, w.lam, causal=causal, ws=ws, out=O)
+            st.synchronize()
+            with torch.cuda.graph(g, stream=st):
+                sp.sparge_forward(Q, K, V, w.tau, w.theta, w.lam, causal=causal, ws=ws, out=O)
+        torch.cuda.synchronize()
+        cases.append((w, Q, K, V, eager.clone(), O, ws, st, g))
+    for rep in range(3):
+        for (_, _, _, _, _, O, ws, _, _) in cases:
+            O.zero_()
+            ws.random_(0, 255)
+        torch.cuda.synchronize()
+        for (_, _, _, _, _, _, _, st, g) in cases:       # both in flight together
+            with torch.cuda.stream(st):
+                g.replay()
+        # an eager call of a third problem on the default stream while the replays run
+        w0, Q0, K0, V0, e0 = cases[0][:5]
+        again = sp.sparge_forward(Q0, K0, V0, w0.tau, w0.theta, w0.lam, causal=w0.causal)
+        torch.cuda.synchronize()
+        assert torch.equal(again, e0)
+        for n, (_, _, _, _, eager, O, _, _, _) in enumerate(cases):
+            assert torch.equal(O, eager), f"round {rep}, graph {n} differs from the eager result"

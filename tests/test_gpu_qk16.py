@@ -9,7 +9,7 @@ import pytest
 
 from oracle import sparge_oracle as so
 from synth import CONFIGS
-from tests.helpers import REF_SLACK, f32, gpu_inputs, small_workload
+from tests.helpers import REF_SLACK, check_output_parity, f32, gpu_inputs, small_workload, to_torch
 
 pytestmark = pytest.mark.gpu
 
@@ -61,6 +61,9 @@ def check(sp, w, x, Q, K, V, mask_np, lam):
         assert e_emul <= REL_L1_EMUL
         if not np.isfinite(lam):
             assert e_exact <= REL_L1_EXACT
+        # per head, row and element against the recurrence as printed and the loop in exact arithmetic
+        check_output_parity(so, O[0, h], q, k, v, m, f32(lam), w.causal, w.dtype, np.arange(w.N), quant=False,
+                            label=f"{w.name} head {h} lambda {lam}")
         assert stats[0, h, 0] == ref.qk_tiles
         assert stats[0, h, 2] == ref.valid_tiles and stats[0, h, 3] == ref.valid_groups
         assert abs(int(stats[0, h, 1]) - ref.pv_groups) <= max(2, ref.pv_groups // 500)
@@ -105,3 +108,27 @@ def test_qk16_unsupported_combinations_raise(sp):
     x, Q, K, V = gpu_inputs(w)
     with pytest.raises(sp.SpargeError):
         sp.sparge_attn(Q, K, V, None, -math.inf, qk16=True, pv_fp8=True)
+
+
+def test_qk16_video_configuration_sampled_rows(sp):
+    """The N = 17550 video configuration in full (48 heads, one sparge_forward call) with the 16-bit Q K^T
+    product: same mask as the INT8 path, counters against the mask, and the output rows of five Q blocks of two
+    heads against the oracle loop without quantization."""
+    import os
+    import torch
+    from synth import make_workload
+    w = CONFIGS["video"]
+    x = make_workload(w, workers=min(16, os.cpu_count() or 1))
+    Q, K, V = (to_torch(x[t], w.dtype) for t in "qkv")
+    O, mask, stats = sp.sparge_forward(Q, K, V, w.tau, w.theta, w.lam, return_mask=True, return_stats=True, qk16=True)
+    mask8 = sp.sparge_predict(Q, K, w.tau, w.theta)
+    assert torch.equal(mask, mask8) and torch.isfinite(O.float()).all()
+    mask_np, stats_np = cpu(mask), cpu(stats)
+    assert (stats_np[0, :, 0] == mask_np[0].reshape(w.H, -1).sum(1)).all()
+    Tm = so.nblocks(w.N, 128)
+    blocks = sorted(set(np.linspace(0, Tm - 1, 5).astype(int).tolist()))
+    rows = np.concatenate([np.arange(128 * i, min(128 * (i + 1), w.N)) for i in blocks])
+    for h in (0, w.H - 1):
+        got = O[0, h].float().cpu().numpy().astype(np.float64)[rows]
+        check_output_parity(so, got, x["q"][0, h], x["k"][0, h], x["v"][0, h], mask_np[0, h], f32(w.lam), False,
+                            w.dtype, rows, q_blocks=blocks, quant=False, label=f"video, 16-bit Q K^T, head {h}")
