@@ -110,6 +110,22 @@ int sparge_predict(const void* Q, const void* K, const sparge_desc* desc,
                    void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
+ * sparge_predict for callers that cannot provide a workspace and must not trigger an allocation: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as
+ * sparge_predict, minus `ws`: the intermediates live in a static device array of the library,
+ * SPARGE_STATIC_SCRATCH_BYTES per device, held until the process ends.  A shape whose predictor workspace
+ * (sparge_workspace_bytes, SPARGE_WS_PREDICT) is larger is rejected with SPARGE_ENOSPACE.  The call
+ * allocates nothing, on the device or through any library.  All calls on one device share that array:
+ * calls that may overlap in time there (different streams or host threads) race and give undefined masks;
+ * nothing in it needs clearing between calls (every intermediate is written before it is read).  The
+ * array's address is looked up at the first call on a device: make that call outside a stream capture.
+ */
+enum { SPARGE_STATIC_SCRATCH_BYTES = 4 << 20 };
+int sparge_predict_static(const void* Q, const void* K, const sparge_desc* desc,
+                          const float* tau, const float* theta, float sm_scale, int causal,
+                          uint8_t* mask, double* sim_q, double* sim_k, void* hip_stream);
+
+/*
  * Sparse flash loop with the stage-2 filter (Alg. 1 lines 7-20; Sec. 3.1, 3.3, 3.4) on
  * pre-quantized Q/K (outputs of sparge_quantize; k_mean is not needed: softmax is invariant to it).
  * For every Q block i and every kept K block j (mask[i,j] != 0, ascending j):

@@ -14,6 +14,8 @@ from .binding import (  # noqa: F401
     sparge_v_tiles,
     sparge_forward,
     sparge_predict,
+    sparge_predict_static,
+    STATIC_SCRATCH_BYTES,
     sparge_hilbert_order,
     sparge_permute_tokens,
     sparge_quantize,

@@ -55,6 +55,8 @@ def load_library() -> ctypes.CDLL:
     lib.sparge_quantize.argtypes = [vp, vp, dp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.sparge_predict.argtypes = [vp, vp, dp, f32p, f32p, ctypes.c_float, ctypes.c_int, vp, vp, vp, vp,
                                    ctypes.c_size_t, vp]
+    lib.sparge_predict_static.argtypes = [vp, vp, dp, f32p, f32p, ctypes.c_float, ctypes.c_int, vp, vp, vp, vp]
+    lib.sparge_predict_static.restype = ctypes.c_int
     lib.sparge_attn_quantized.argtypes = [vp, vp, vp, vp, vp, dp, vp, f32p, ctypes.c_float, ctypes.c_int, vp, vp,
                                           vp, ctypes.c_size_t, vp]
     lib.sparge_v_tiles.argtypes = [vp, dp, vp, vp]
@@ -190,6 +192,21 @@ def sparge_predict(Q: torch.Tensor, K: torch.Tensor, tau, theta, causal: bool = 
                                          float(sm_scale), int(causal), _ptr(mask), _ptr(sq), _ptr(sk), _ptr(ws),
                                          ws.numel(), _stream()))
     return (mask, sq, sk) if return_sims else mask
+
+
+STATIC_SCRATCH_BYTES = 4 << 20  # SPARGE_STATIC_SCRATCH_BYTES
+
+
+def sparge_predict_static(Q: torch.Tensor, K: torch.Tensor, tau, theta, mask: torch.Tensor, causal: bool = False,
+                          sm_scale: float = 0.0, sim_q: Optional[torch.Tensor] = None,
+                          sim_k: Optional[torch.Tensor] = None) -> None:
+    """sparge_predict without a workspace (the library's static scratch).  Nothing is allocated here either:
+    the caller passes `mask` (uint8 [B,H,Tm,Tn]) and, optionally, sim_q / sim_k (fp64)."""
+    _same_layout(Q, K)
+    d = _desc(Q)
+    _check(load_library().sparge_predict_static(_ptr(Q), _ptr(K), ctypes.byref(d), _per_head(tau, Q.shape[1]),
+                                                _per_head(theta, Q.shape[1]), float(sm_scale), int(causal),
+                                                _ptr(mask), _ptr(sim_q), _ptr(sim_k), _stream()))
 
 
 def sparge_attn_quantized(Qq, Kq, q_scale, k_scale, V: torch.Tensor, mask: Optional[torch.Tensor], lam,

@@ -13,6 +13,11 @@
 
 using namespace sparge;
 
+// Scratch of sparge_predict_static: the predictor's intermediates for callers that cannot pass a workspace.
+// Every device the library runs on holds its own copy at its own address; host code never uses this name as
+// an address, only the pointer hipGetSymbolAddress returns for the current device (static_scratch below).
+static __device__ __align__(256) unsigned char scratch[SPARGE_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 thread_local char g_err[512] = "";
@@ -196,6 +201,25 @@ SideStream* side_stream() {
     return x.stream ? &x : nullptr;
 }
 
+// Device address of `scratch` on the current device: looked up once per device, with that device current.
+void* g_scratch_ptr[MAX_DEVICES];
+std::mutex g_scratch_mutex;
+int static_scratch(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(SPARGE_EUNSUPPORTED, "device %d: more devices than the library tracks", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return SPARGE_OK;
+}
+
 int run_stats_and_quant(const void* Q, const void* K, const Shape& s, double* pooled_q, double* ksum_t,
                         double* sim_q, double* sim_k, int8_t* Qq, float* q_scale, int8_t* Kq, float* k_scale,
                         float* k_mean, hipStream_t st) {
@@ -305,6 +329,22 @@ int sparge_predict(const void* Q, const void* K, const sparge_desc* desc, const 
     if (sim_k && (e = hipMemcpyAsync(sim_k, at<double>(ws, w.sim_k), BH * s.Tn * sizeof(double),
                                      hipMemcpyDeviceToDevice, st)) != hipSuccess) return hip_fail(e, "copy sim_k");
     return SPARGE_OK;
+}
+
+int sparge_predict_static(const void* Q, const void* K, const sparge_desc* desc, const float* tau,
+                          const float* theta, float sm_scale, int causal, uint8_t* mask, double* sim_q,
+                          double* sim_k, void* hip_stream) {
+    Shape s;
+    int rc = check_desc(desc, &s);
+    if (rc) return rc;
+    const size_t need = plan(s, SPARGE_WS_PREDICT).total;
+    if (need > SPARGE_STATIC_SCRATCH_BYTES)
+        return fail(SPARGE_ENOSPACE, "sparge_predict_static: this shape needs %zu bytes of scratch, the static buffer has %zu; "
+                    "use sparge_predict with a workspace", need, (size_t)SPARGE_STATIC_SCRATCH_BYTES);
+    void* ws = nullptr;
+    if ((rc = static_scratch(&ws))) return rc;
+    return sparge_predict(Q, K, desc, tau, theta, sm_scale, causal, mask, sim_q, sim_k, ws,
+                          SPARGE_STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 int sparge_attn_quantized(const int8_t* Qq, const int8_t* Kq, const float* q_scale, const float* k_scale,
