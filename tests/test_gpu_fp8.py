@@ -2,9 +2,11 @@
 
 Bars: the E4M3 tiles of V and the channel scales bit-exact; outputs within relative L1 2e-3 of the
 oracle that emulates the same quantization and rounding points (pv_dtype="fp8e4m3", the same lag of
-the reference maximum), and within 8e-2 of exact fp64 attention on the same blocks: two roundings
-with unit roundoff 2^-4 per product, averaged over the keys a row attends to (the 16-bit product's
-bar is 3e-2).
+the reference maximum), and within one unit roundoff of E4M3, u = 2^-4 = 6.25e-2, of exact fp64 attention on
+the same blocks: P~ and V-hat are each rounded once to 4 significant bits (relative error of rms 0.4247 u for a
+log-uniform significand), which for outputs that are random combinations of V rows gives a relative L1
+distance of sqrt(2) * 0.4247 u = 0.60 u = 3.75e-2 (measured 3.5e-2 ... 4.2e-2); the bar leaves the same
+room as the 16-bit product's bars in tests/helpers.py (the benchmark spec's 3e-2 belongs to the 16-bit product).
 """
 import math
 
@@ -18,7 +20,7 @@ from tests.helpers import f32, gpu_inputs, small_workload
 pytestmark = pytest.mark.gpu
 
 REL_L1_EMUL = 2e-3
-REL_L1_EXACT_FP8 = 8e-2
+REL_L1_EXACT_FP8 = 2.0 ** -4
 
 
 @pytest.fixture(scope="module")
