@@ -54,7 +54,7 @@ enum { SPARGE_PV_16BIT = 0 /* the tensors' fp16/bf16 */, SPARGE_PV_FP8 = 1 /* OC
  * "SpargeAttn+FA2" variant (Sec. 4.3): the same two-stage filter on an unquantized kernel -- Q and K
  * enter the product as they are (no K smoothing is needed: it does not change the softmax), scores
  * accumulate in fp32, S = Q_i K_j^T * sm_scale.  Read by sparge_attn and sparge_forward only; not built
- * together with SPARGE_PV_FP8, for N <= 65536. */
+ * together with SPARGE_PV_FP8, for N <= 131072 (2048 key blocks). */
 enum { SPARGE_QK_INT8 = 0, SPARGE_QK_16BIT = 1 };
 
 /* which entry point a workspace is sized for */

@@ -61,7 +61,7 @@ int check_desc(const sparge_desc* d, Shape* s) {
         return fail(SPARGE_EUNSUPPORTED, "qk_dtype %d not supported", d->qk_dtype);
     s->qk16 = d->qk_dtype == SPARGE_QK_16BIT;
     if (s->qk16 && s->pv_fp8) return fail(SPARGE_EUNSUPPORTED, "the 16-bit Q K^T product is not built with the FP8 P~V product");
-    if (s->qk16 && Tn > 1024) return fail(SPARGE_EUNSUPPORTED, "the 16-bit Q K^T product takes at most 1024 key blocks (N <= 65536)");
+    if (s->qk16 && Tn > 2048) return fail(SPARGE_EUNSUPPORTED, "the 16-bit Q K^T product takes at most 2048 key blocks (N <= 131072)");
     if (s->qk16 && (double)Tn * BK * d->stride_n * 2.0 >= 4294967296.0)
         return fail(SPARGE_EUNSUPPORTED, "the 16-bit Q K^T product needs a head's K to span less than 4 GiB");
     return SPARGE_OK;

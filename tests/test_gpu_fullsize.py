@@ -118,10 +118,12 @@ def test_full_configuration(sp, name):
     assert err8 <= 2e-3
 
 
-@pytest.mark.parametrize("causal,dtype,d,pv_fp8", [(False, "bf16", 128, False), (True, "fp16", 64, False),
-                                                   (False, "fp16", 128, True), (True, "bf16", 64, True)])
-def test_long_list_two_stage_kernel(sp, causal, dtype, d, pv_fp8):
-    """T_n > 1024 selects the kernel variant with two LDS stages and the long tile list: N = 70 000
+@pytest.mark.parametrize("causal,dtype,d,pv_fp8,qk16", [(False, "bf16", 128, False, False), (True, "fp16", 64, False, False),
+                                                        (False, "fp16", 128, True, False), (True, "bf16", 64, True, False),
+                                                        (True, "bf16", 128, False, True), (False, "fp16", 64, False, True)])
+def test_long_list_two_stage_kernel(sp, causal, dtype, d, pv_fp8, qk16):
+    """T_n > 1024 selects the kernel variants with two LDS stages and the long tile list (2048 entries for the
+    16-bit Q K^T product, whose K tiles are twice as large, 4096 otherwise): N = 70 000
     (ragged: last Q block 112 rows, last K block 48 keys), one head, a random block mask with a forced
     first column (and diagonal when causal); the output rows of a few Q blocks against the oracle loop."""
     import torch
@@ -139,23 +141,23 @@ def test_long_list_two_stage_kernel(sp, causal, dtype, d, pv_fp8):
         mask_np[0, 0, np.arange(Tm), np.minimum(2 * np.arange(Tm), Tn - 1)] = 1
     mask_np[0, 0, -1, -1] = 1   # the partial last key block is used by the ragged last Q block
     mask_t = torch.from_numpy(mask_np).to("cuda")
-    O, stats = sp.sparge_attn(Q, K, V, mask_t, w.lam, causal=causal, return_stats=True, pv_fp8=pv_fp8)
+    O, stats = sp.sparge_attn(Q, K, V, mask_t, w.lam, causal=causal, return_stats=True, pv_fp8=pv_fp8, qk16=qk16)
     torch.cuda.synchronize()
     assert torch.isfinite(O.float()).all()
     q, k, v = x["q"][0, 0], x["k"][0, 0], x["v"][0, 0]
     blocks = [0, 1, Tm // 3, Tm - 2, Tm - 1]
-    ref = so.sparse_attention(q, k, v, mask_np[0, 0], lam=f32(w.lam), causal=causal, quant=True,
+    ref = so.sparse_attention(q, k, v, mask_np[0, 0], lam=f32(w.lam), causal=causal, quant=not qk16,
                               pv_dtype="fp8e4m3" if pv_fp8 else dtype, q_blocks=blocks,
                               ref_slack=sp.REF_SLACK_LOG2_FP8 * math.log(2.0) if pv_fp8 else REF_SLACK)
     assert ref.zero_rows == 0
     rows = np.concatenate([np.arange(128 * i, min(128 * (i + 1), N)) for i in blocks])
     got = O[0, 0].float().cpu().numpy().astype(np.float64)[rows]
     err = so.rel_l1(got, so.round16(ref.O[rows], dtype))
-    print(f"  long list causal={causal} fp8={pv_fp8}: rel-L1 vs oracle {err:.2e}", flush=True)
+    print(f"  long list causal={causal} fp8={pv_fp8} qk16={qk16}: rel-L1 vs oracle {err:.2e}", flush=True)
     assert err <= 2e-3
     if not pv_fp8:
         check_output_parity(so, got, q, k, v, mask_np[0, 0], f32(w.lam), causal, dtype, rows, q_blocks=blocks,
-                            label=f"long list causal={causal}")
+                            label=f"long list causal={causal} qk16={qk16}", quant=not qk16)
     tiles, groups = closed_form_valid(N, causal)
     s = stats.cpu().numpy()[0, 0]
     assert s[2] == tiles and s[3] == groups
