@@ -108,6 +108,18 @@ def test_compressed_map_all_columns_masked_gives_zero_row():
     assert np.all(P == 0)
 
 
+def test_compressed_map_is_stable_for_large_logits():
+    """Row softmax with the maximum subtracted: logits of +-3000 neither overflow nor lose the runner-up."""
+    q = np.array([[30.0, 0.0], [0.0, -30.0]])
+    k = np.array([[100.0, 0.0], [99.9, 0.0], [0.0, 100.0], [-100.0, 100.0]])
+    P = so.compressed_map(q, k, np.ones(4), 0.0, 1.0, False)
+    assert np.isfinite(P).all()
+    np.testing.assert_allclose(P.sum(axis=1), 1.0, atol=1e-14)
+    np.testing.assert_allclose(P[0, 1] / P[0, 0], math.exp(-3.0), rtol=1e-12)
+    assert P[0, 2] == 0.0 and P[0, 3] == 0.0
+    np.testing.assert_allclose(P[1, :2], 0.5, atol=1e-14)           # logits 0, 0, -3000, -3000
+
+
 def test_compressed_map_scale_matters_and_causal_future_is_zero():
     q = rng(11).standard_normal((2, 8))
     k = rng(12).standard_normal((4, 8))
@@ -170,6 +182,36 @@ def test_topcdf_top_value_above_tau_keeps_exactly_it_and_zeros_never_kept():
     assert not m.any()
 
 
+def test_topcdf_stops_when_the_mass_before_an_entry_equals_the_target():
+    """The prefix is the smallest one that reaches tau * sum: an entry whose preceding mass equals the target
+    exactly is not kept.  Exact binary fractions, so no rounding blurs the comparison."""
+    mask, _ = so.top_cdf(np.array([0.5, 0.25, 0.25]), 0.5)
+    assert mask.tolist() == [True, False, False]
+    mask, _ = so.top_cdf(np.array([0.125, 0.5, 0.125, 0.25]), 0.75)        # ranks: 0.5, 0.25 | 0.125, 0.125
+    assert mask.tolist() == [False, True, False, True]
+    mask, _ = so.top_cdf(np.array([0.125, 0.5, 0.125, 0.25]), 0.75 + 2.0 ** -40)
+    assert mask.tolist() == [True, True, False, True]
+
+
+def test_topcdf_with_tau_one_keeps_every_positive_entry_and_no_zero():
+    """tau = 1: the positive support (entries so small that the running sum no longer moves may fall to the
+    rounding of the sums, and are flagged), and never an entry of probability zero -- also when the prefix sums,
+    accumulated in another order than the total, stay a rounding error below it."""
+    r = rng(12)
+    seen_short = False
+    for _ in range(300):
+        n = int(r.integers(50, 400))
+        p = r.random(n) ** 8
+        p[r.random(n) < 0.3] = 0.0
+        p /= p.sum()
+        mask, dc = so.top_cdf(p, 1.0)
+        assert not mask[p == 0].any()                 # a zero is never selected ...
+        assert (mask | dc | (p == 0)).all()           # ... and a positive entry is dropped only inside the rounding band
+        sp = np.sort(p)[::-1]
+        seen_short |= np.cumsum(sp)[(p > 0).sum() - 1] < sp.sum()       # the case in which a zero could slip in
+    assert seen_short
+
+
 def test_topcdf_dont_care_flags_threshold_hits():
     p = np.array([0.5, 0.25, 0.25])
     m, dc = so.top_cdf(p, 0.5)       # mass before rank 1 equals tau*sum exactly
@@ -219,6 +261,22 @@ def test_predict_overrides_and_pure_topcdf():
         assert (pr2.mask[i] == exp).all()
     # theta > 1: every block is a fix block -> all ones
     assert so.predict(Q, K, tau=0.5, theta=1.5).mask.all()
+
+
+def test_predict_fix_rows_are_decided_whatever_topcdf_says():
+    """A Q block that is not self-similar keeps its whole row: nothing in it is undecided, even when the row's
+    TopCdf sits exactly on its threshold (uniform P-hat, tau * n an integer)."""
+    r = rng(27)
+    d = 16
+    K = _blocks_with_similarity(r, 8, so.BK, d, [True] * 8)
+    Q = _blocks_with_similarity(r, 2, so.BQ, d, [True, False])
+    Q[so.BQ:] -= Q[so.BQ:].mean(axis=0)          # pooled token of block 1 is zero: its P-hat row is uniform
+    pr = so.predict(Q, K, tau=0.5, theta=0.5)
+    assert pr.sim_q[1] < 0.5 < pr.sim_q[0]
+    np.testing.assert_allclose(pr.p_hat[1], 1.0 / 8.0, atol=1e-12)
+    _, flagged = so.top_cdf(pr.p_hat[1], 0.5)
+    assert flagged.any()                          # TopCdf alone would call this row undecided ...
+    assert pr.mask[1].all() and not pr.dont_care[1].any()      # ... the fix-block rule decides it
 
 
 def test_predict_causal_rules():
@@ -411,6 +469,14 @@ def test_k_mean_is_exact_sum_over_n():
     for c in range(3):
         exact = sum(Fraction(float(v)) for v in K[:, c]) / 130
         assert float(mean[c]) == float(np.float32(float(exact)))
+    # thousands of terms of mixed magnitude and sign: a sum that rounds along the way (fp32, or fp64 in an
+    # unlucky order) no longer lands on the correctly rounded mean in every channel
+    r = rng(26)
+    K = as16(r.standard_normal((6000, 8)) * np.exp2(r.integers(-12, 13, size=(6000, 8))) + 3.0, "bf16")
+    mean = so.k_mean(K)
+    for c in range(8):
+        exact = sum(Fraction(float(v)) for v in K[:, c]) / 6000
+        assert float(mean[c]) == float(np.float32(exact.numerator / exact.denominator))
 
 
 # ------------------------------------------------------------------ dense reference vs textbook
@@ -556,10 +622,19 @@ def test_lambda_threshold_is_strict_and_per_row_group():
     for lam, expect in ((-1.0, 4 + 0), (-2.0, 4 + 0), (-2.5, 4 + 1), (-4.0, 4 + 1), (-4.5, 4 + 2), (-100.0, 8)):
         res = so.sparse_attention(Q, K, V, None, lam=lam, scale=1.0, quant=False)
         assert res.pv_groups == expect, (lam, res.pv_groups)
+    # sparsity counts both kinds of skipped products (Sec. 4.1): here both tiles run, 5 of 8 row-group products do
+    res = so.sparse_attention(Q, K, V, None, lam=-2.5, scale=1.0, quant=False)
+    assert (res.qk_tiles, res.valid_tiles, res.pv_groups, res.valid_groups) == (2, 2, 5, 8)
+    assert res.sparsity == pytest.approx(1.0 - 0.5 * (1.0 + 5.0 / 8.0))
     # the reported distance of the statistic from lambda: tile 0 has m_local - m = 0, tile 1 has -2(w+1)
     res = so.sparse_attention(Q, K, V, None, lam=-4.25, scale=1.0, quant=False)
     np.testing.assert_allclose(res.lam_margin[0], [2.25, 0.25, 1.75, 3.75], atol=1e-12)
     assert np.isinf(so.sparse_attention(Q, K, V, None, scale=1.0, quant=False).lam_margin).all()
+    K2 = K.copy()
+    K2[:64, 0] = 1.0                  # tile 0 scores 2(w+1), tile 1 scores -2(w+1): the statistic is -4(w+1), not m_local
+    res = so.sparse_attention(Q, K2, V, None, lam=-9.0, scale=1.0, quant=False)
+    np.testing.assert_allclose(res.lam_margin[0], [5.0, 1.0, 3.0, 7.0], atol=1e-12)
+    assert res.pv_groups == 4 + 2
     # l is updated even for skipped groups: output = sum over block 0 of V / (64 + 64 e^{-2(w+1)})
     res = so.sparse_attention(Q, K, V, None, lam=-1.0, scale=1.0, quant=False)
     for w in range(4):
@@ -811,6 +886,9 @@ def test_tuner_limits():
     assert tight.l1 == pytest.approx(tight.stage1[..., 1].min())
     mid = so.tune_head(inputs, taus, thetas, lams, 0.05, 0.05)
     assert tight.sparsity - 1e-12 <= mid.sparsity <= loose.sparsity + 1e-12
+    # a lambda that never skips anything does not beat leaving the stage-2 test off: it is not taken
+    same = so.tune_head(inputs, taus, thetas, [-1e9], 10.0, 10.0)
+    assert same.lam == -np.inf and same.stage2[0, 0] == pytest.approx(same.sparsity)
     # a single-entry grid with tau = 1, theta > 1 is full attention: zero error, zero sparsity
     one = so.tune_head(inputs, [1.0], [2.0], [], 0.01, 0.01)
     assert one.sparsity == 0.0 and one.l1 == 0.0
