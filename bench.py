@@ -205,7 +205,12 @@ def parity_sample(w, data, mask_gpu, O_gpu, blocks):
     rows = np.concatenate([np.arange(128 * i, min(128 * (i + 1), w.N)) for i in blocks])
     ref, got = so.round16(res.O[rows], w.dtype), O_gpu[rows]
     den = np.abs(ref).sum(axis=1)
+    # and against attention in plain fp64 on the same blocks with the same lambda: what quantization and the 16-bit
+    # product add together
+    plain = so.sparse_attention(q, k, v, mask_gpu[0, 0], lam=float(np.float32(w.lam)), causal=w.causal, quant=False,
+                                pv_dtype="none", q_blocks=blocks)
     return {"rel_l1": so.rel_l1(got, ref), "rel_l1_worst_row": float((np.abs(got - ref).sum(axis=1) / np.where(den > 0, den, 1.0)).max()),
+            "rel_l1_vs_unquantized_fp64_same_blocks": so.rel_l1(got, plain.O[rows]),
             "rows": int(len(rows)), "q_blocks": [int(b) for b in blocks], "head": 0,
             "reference": "fp64 oracle of Alg. 1 with the same INT8 quantization, block mask and P~ rounding point"}
 
@@ -233,7 +238,12 @@ def cpu_baseline(w, data, mask_gpu, O_gpu, budget_blocks=None):
     rowsel = np.concatenate([np.arange(128 * i, min(128 * (i + 1), w.N)) for i in blocks])
     ref16 = so.round16(res.O[rowsel], w.dtype)
     den = np.abs(ref16).sum(axis=1)
+    few = blocks[::max(1, len(blocks) // 4)][:4]        # a few of the sampled blocks once more, in plain fp64
+    plain = so.sparse_attention(q, k, v, mask_gpu[0, 0], lam=float(np.float32(w.lam)), causal=w.causal, quant=False,
+                                pv_dtype="none", q_blocks=few)
+    fewrows = np.concatenate([np.arange(128 * i, min(128 * (i + 1), w.N)) for i in few])
     parity = {"rel_l1": so.rel_l1(O_gpu[rowsel], ref16),
+              "rel_l1_vs_unquantized_fp64_same_blocks": so.rel_l1(O_gpu[fewrows], plain.O[fewrows]),
               "rel_l1_worst_row": float((np.abs(O_gpu[rowsel] - ref16).sum(axis=1) / np.where(den > 0, den, 1.0)).max()),
               "rows": int(len(rowsel)), "head": 0,
               "reference": "fp64 oracle of Alg. 1 with the same INT8 quantization, block mask and P~ rounding point"}

@@ -182,3 +182,30 @@ def test_rows_longer_than_2048_blocks(sp, causal):
     s = cpu(stats)[0, 0]
     visible = mask[0, 0].astype(bool)
     assert s[0] == visible.sum()
+
+
+def test_longest_rows_the_library_takes(sp):
+    """T_n = SPARGE_MAX_TN = 4096 (N = 262 144, T_m = 2048), one head, d = 64, fp16: the predictor against the
+    oracle and the output rows of four Q blocks, one of them a fix block whose list holds all 4096 key blocks
+    (four chunks of the list build, the whole list capacity of the kernel)."""
+    N = 64 * 4096
+    w = small_workload("maxlen", N=N, d=64, dtype="fp16", H=1, seed=47, segment=1536, noise=0.35,
+                       tau=0.7, theta=0.45, lam=-6.0)
+    x = make_workload(w)
+    Tm = so.nblocks(N, 128)
+    x["q"][0, 0, 128 * 1000:128 * 1001] = so.round16(np.random.default_rng(48).standard_normal((128, 64)), w.dtype)
+    Q, K, V = (to_torch(x[t], w.dtype) for t in "qkv")
+    q, k, v = x["q"][0, 0], x["k"][0, 0], x["v"][0, 0]
+    print("  oracle predictor ...", flush=True)
+    pr = so.predict(q, k, f32(w.tau), f32(w.theta))
+    O, mask, stats = sp.sparge_forward(Q, K, V, w.tau, w.theta, w.lam, return_mask=True, return_stats=True)
+    mask, O = cpu(mask), cpu(O).astype(np.float64)
+    bad = (mask[0, 0] != pr.mask) & ~pr.dont_care
+    print(f"  kept {mask.mean():.3f}, dont-care {int(pr.dont_care.sum())}", flush=True)
+    assert not bad.any(), np.argwhere(bad)[:5]
+    assert pr.dont_care.mean() < 0.01 and mask[0, 0, 1000].sum() == 4096
+    assert np.isfinite(O).all() and cpu(stats)[0, 0, 0] == mask.sum()
+    blocks = [0, 1000, Tm // 2 + 1, Tm - 1]
+    rows = np.concatenate([np.arange(128 * i, 128 * (i + 1)) for i in blocks])
+    check_output_parity(so, O[0, 0][rows], q, k, v, mask[0, 0], f32(w.lam), False, w.dtype, rows, q_blocks=blocks,
+                        label=f"N={N}")
