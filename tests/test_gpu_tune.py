@@ -97,3 +97,20 @@ def test_tuner_matches_the_oracle(sp, causal, dtype, d, pv_fp8):
                     assert got["lam"][h] == (f32(ref.lam) if np.isfinite(ref.lam) else -math.inf)
             assert got["sparsity"][h] == pytest.approx(ref.sparsity, abs=2 * TOL_SPARSITY)
         assert got["l1"][h] < l2 + TOL_L1
+
+
+def test_rel_l1_and_tuner_are_reproducible(sp):
+    """The error sums are reduced in a fixed order: the same inputs give the same bits on every call, and the
+    search, which compares those sums with its bounds, returns identical tables and choices."""
+    import torch
+    ws = [small_workload(f"rep{i}", N=3000, d=128, dtype="bf16", H=3, seed=60 + i, noise=0.6) for i in range(2)]
+    xs = [make_workload(w) for w in ws]
+    inputs = [tuple(to_torch(x[t], "bf16") for t in "qkv") for x in xs]
+    a, b = inputs[0][2], inputs[1][2]
+    first = sp.sparge_rel_l1(a, b)
+    for _ in range(5):
+        assert torch.equal(sp.sparge_rel_l1(a, b), first)
+    runs = [sp.sparge_tune(inputs, [0.6, 0.9], [0.3, 0.6], [-6.0, -3.0], 0.05, 0.06) for _ in range(3)]
+    for r in runs[1:]:
+        assert np.array_equal(r["stage1"], runs[0]["stage1"]) and np.array_equal(r["stage2"], runs[0]["stage2"])
+        assert r["tau"] == runs[0]["tau"] and r["theta"] == runs[0]["theta"] and r["lam"] == runs[0]["lam"]
