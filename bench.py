@@ -209,8 +209,11 @@ def parity_sample(w, data, mask_gpu, O_gpu, blocks):
     # product add together
     plain = so.sparse_attention(q, k, v, mask_gpu[0, 0], lam=float(np.float32(w.lam)), causal=w.causal, quant=False,
                                 pv_dtype="none", q_blocks=blocks)
+    # and against full attention (every block, no lambda) in fp64: the error measure of the paper's tables (Sec. 3.6)
+    full = so.sparse_attention(q, k, v, None, causal=w.causal, quant=False, pv_dtype="none", q_blocks=blocks)
     return {"rel_l1": so.rel_l1(got, ref), "rel_l1_worst_row": float((np.abs(got - ref).sum(axis=1) / np.where(den > 0, den, 1.0)).max()),
             "rel_l1_vs_unquantized_fp64_same_blocks": so.rel_l1(got, plain.O[rows]),
+            "rel_l1_vs_full_attention_fp64": so.rel_l1(got, full.O[rows]),
             "rows": int(len(rows)), "q_blocks": [int(b) for b in blocks], "head": 0,
             "reference": "fp64 oracle of Alg. 1 with the same INT8 quantization, block mask and P~ rounding point"}
 
@@ -242,8 +245,11 @@ def cpu_baseline(w, data, mask_gpu, O_gpu, budget_blocks=None):
     plain = so.sparse_attention(q, k, v, mask_gpu[0, 0], lam=float(np.float32(w.lam)), causal=w.causal, quant=False,
                                 pv_dtype="none", q_blocks=few)
     fewrows = np.concatenate([np.arange(128 * i, min(128 * (i + 1), w.N)) for i in few])
+    # and against full attention (every block, no lambda) in fp64: the error measure of the paper's tables (Sec. 3.6)
+    full = so.sparse_attention(q, k, v, None, causal=w.causal, quant=False, pv_dtype="none", q_blocks=few)
     parity = {"rel_l1": so.rel_l1(O_gpu[rowsel], ref16),
               "rel_l1_vs_unquantized_fp64_same_blocks": so.rel_l1(O_gpu[fewrows], plain.O[fewrows]),
+              "rel_l1_vs_full_attention_fp64": so.rel_l1(O_gpu[fewrows], full.O[fewrows]),
               "rel_l1_worst_row": float((np.abs(O_gpu[rowsel] - ref16).sum(axis=1) / np.where(den > 0, den, 1.0)).max()),
               "rows": int(len(rowsel)), "head": 0,
               "reference": "fp64 oracle of Alg. 1 with the same INT8 quantization, block mask and P~ rounding point"}

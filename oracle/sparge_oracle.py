@@ -211,6 +211,24 @@ def predict(Q: np.ndarray, K: np.ndarray, tau: float, theta: float, scale: Optio
     return Prediction(mask.astype(np.uint8), dc, s_q, s_k, q, k, P)
 
 
+def mask_to_lut(mask: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """The block mask M_g (Sec. 3.2, Def. 2) of one head as an index list: row i of `lut` holds the key
+    blocks j with M_g[i, j] = 1 in ascending order, then -1 up to T_n entries; count[i] is their number.
+    (The loop of Alg. 1 visits exactly these j, in this order, for Q block i.)"""
+    mask = np.asarray(mask)
+    Tm, Tn = mask.shape
+    lut = np.full((Tm, Tn), -1, dtype=np.int32)
+    count = np.zeros(Tm, dtype=np.int32)
+    for i in range(Tm):
+        n = 0
+        for j in range(Tn):
+            if mask[i, j]:
+                lut[i, n] = j
+                n += 1
+        count[i] = n
+    return lut, count
+
+
 # ----------------------------------------------------------------------------------------------
 # Quant (Alg. 1 line 3): per-block symmetric INT8, K smoothed by its token mean
 # ----------------------------------------------------------------------------------------------

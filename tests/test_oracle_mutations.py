@@ -58,6 +58,8 @@ MUTATIONS = [
     ("Hilbert curve without the Gray decoding", "    X[0] ^= t\n", "    pass\n"),
     ("inverse token permutation equals the forward one", "Y[offset + np.asarray(perm)] = X[offset:offset + L]", "Y[offset:offset + L] = X[offset + np.asarray(perm)]"),
     ("row groups that see no key of a causal tile counted as work", "if not causal or c0 <= last_row:", "if True:"),
+    ("index list stores the position instead of the block", "                lut[i, n] = j\n", "                lut[i, n] = n\n"),
+    ("index list count is the last kept block", "        count[i] = n\n", "        count[i] = lut[i, max(n - 1, 0)]\n"),
     ("reference moves only when every row of the group ran ahead", "if np.any(ahead > ref_slack):", "if np.all(ahead > ref_slack):"),
     ("reference moves per row instead of per row group", "                    m_ref[g0:g1] = m_new[g0:g1]\n",
      "                    m_ref[g0:g1] = np.where(ahead > ref_slack, m_new[g0:g1], m_ref[g0:g1])\n"),

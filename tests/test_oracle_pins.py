@@ -940,3 +940,21 @@ def test_token_permutation_round_trip_and_attention_invariance():
     O = so.dense_attention(Q, K, V)
     Op = so.dense_attention(*(so.permute_tokens(T, perm, off) for T in (Q, K, V)))
     np.testing.assert_allclose(so.permute_tokens(Op, perm, off, inverse=True), O, rtol=0, atol=1e-12)
+
+
+def test_mask_to_lut_literal_and_round_trip():
+    """Index-list form of M_g: a literal case, and the properties that define it on random masks."""
+    m = np.array([[1, 0, 1, 1], [0, 0, 0, 0], [0, 1, 0, 0]], dtype=np.uint8)
+    lut, cnt = so.mask_to_lut(m)
+    assert lut.tolist() == [[0, 2, 3, -1], [-1, -1, -1, -1], [1, -1, -1, -1]]
+    assert cnt.tolist() == [3, 0, 1]
+    rng = np.random.default_rng(5)
+    m = (rng.random((37, 150)) < 0.3).astype(np.uint8)
+    lut, cnt = so.mask_to_lut(m)
+    assert np.array_equal(cnt, m.sum(axis=1))
+    back = np.zeros_like(m)
+    for i in range(m.shape[0]):
+        js = lut[i, :cnt[i]]
+        assert (np.diff(js) > 0).all() and (lut[i, cnt[i]:] == -1).all()
+        back[i, js] = 1
+    assert np.array_equal(back, m)
