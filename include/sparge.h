@@ -154,6 +154,16 @@ int sparge_attn_quantized(const int8_t* Qq, const int8_t* Kq, const float* q_sca
                           void* O, uint64_t* stats, void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
+ * The block mask M_g (Sec. 3.2, Def. 2) as an index list, for callers whose own kernels walk lists of kept
+ * blocks: lut int32 [B,H,T_m,T_n], row (b,h,i) holds the j with mask[b,h,i,j] != 0 in ascending order -- the
+ * order in which Alg. 1 line 9 visits them -- followed by -1; lut_count int32 [B,H,T_m] their number.
+ * mask: uint8 [B,H,T_m,T_n] as sparge_predict writes it.  All three are device memory.  (The library's own
+ * attention kernel builds this list per Q block in LDS and does not need the call.)
+ */
+int sparge_mask_to_lut(const uint8_t* mask, const sparge_desc* desc, int32_t* lut, int32_t* lut_count,
+                       void* hip_stream);
+
+/*
  * The two halves of sparge_attn_quantized, for callers that reuse V across calls or time the loop
  * alone.  sparge_v_tiles re-tiles V for the P~V product (Alg. 1 line 16); sparge_v_tiles_bytes gives
  * the size of its output (16-byte aligned device memory).

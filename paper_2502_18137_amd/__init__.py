@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     sparge_attn,
     sparge_attn_quantized,
     sparge_attn_tiled,
+    sparge_mask_to_lut,
     sparge_v_tiles,
     sparge_forward,
     sparge_predict,

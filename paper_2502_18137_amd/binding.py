@@ -59,6 +59,7 @@ def load_library() -> ctypes.CDLL:
     lib.sparge_predict_static.restype = ctypes.c_int
     lib.sparge_attn_quantized.argtypes = [vp, vp, vp, vp, vp, dp, vp, f32p, ctypes.c_float, ctypes.c_int, vp, vp,
                                           vp, ctypes.c_size_t, vp]
+    lib.sparge_mask_to_lut.argtypes = [vp, dp, vp, vp, vp]
     lib.sparge_v_tiles.argtypes = [vp, dp, vp, vp]
     lib.sparge_v_tiles_bytes.argtypes = [dp, ctypes.POINTER(ctypes.c_size_t)]
     lib.sparge_attn_tiled.argtypes = [vp, vp, vp, vp, vp, dp, vp, f32p, ctypes.c_float, ctypes.c_int, vp, vp, vp,
@@ -79,7 +80,7 @@ def load_library() -> ctypes.CDLL:
     lib.sparge_forward.argtypes = [vp, vp, vp, dp, f32p, f32p, f32p, ctypes.c_float, ctypes.c_int, vp, vp, vp, vp,
                                    ctypes.c_size_t, vp]
     for name in ("sparge_workspace_bytes", "sparge_quantize", "sparge_predict", "sparge_attn_quantized",
-                 "sparge_attn", "sparge_forward", "sparge_v_tiles", "sparge_attn_tiled", "sparge_v_tiles_bytes",
+                 "sparge_attn", "sparge_forward", "sparge_mask_to_lut", "sparge_v_tiles", "sparge_attn_tiled", "sparge_v_tiles_bytes",
                  "sparge_rel_l1", "sparge_tune_workspace_bytes", "sparge_tune", "sparge_hilbert_order",
                  "sparge_permute_tokens"):
         getattr(lib, name).restype = ctypes.c_int
@@ -233,6 +234,20 @@ def sparge_attn_quantized(Qq, Kq, q_scale, k_scale, V: torch.Tensor, mask: Optio
                                                 ctypes.byref(d), _ptr(mask), _per_head(lam, H), float(sm_scale),
                                                 int(causal), _ptr(O), _ptr(stats), _ptr(ws), ws.numel(), _stream()))
     return (O, stats) if return_stats else O
+
+
+def sparge_mask_to_lut(mask: torch.Tensor, like: torch.Tensor):
+    """-> (lut int32 [B,H,Tm,Tn]: kept key blocks of each row ascending, then -1; count int32 [B,H,Tm]).
+    `like`: a tensor of the attention shape [B,H,N,d] the mask belongs to."""
+    d = _desc(like)
+    B, H, N, _ = like.shape
+    Tm, Tn = _blocks(N)
+    if tuple(mask.shape) != (B, H, Tm, Tn) or mask.dtype != torch.uint8 or not mask.is_contiguous() or mask.device != like.device:
+        raise SpargeError("mask must be a contiguous uint8 [B,H,Tm,Tn] tensor")
+    lut = torch.empty((B, H, Tm, Tn), dtype=torch.int32, device=mask.device)
+    count = torch.empty((B, H, Tm), dtype=torch.int32, device=mask.device)
+    _check(load_library().sparge_mask_to_lut(_ptr(mask), ctypes.byref(d), _ptr(lut), _ptr(count), _stream()))
+    return lut, count
 
 
 def sparge_v_tiles(V: torch.Tensor, pv_fp8: bool = False) -> torch.Tensor:

@@ -347,6 +347,17 @@ int sparge_predict_static(const void* Q, const void* K, const sparge_desc* desc,
                           SPARGE_STATIC_SCRATCH_BYTES, hip_stream);
 }
 
+int sparge_mask_to_lut(const uint8_t* mask, const sparge_desc* desc, int32_t* lut, int32_t* lut_count, void* hip_stream) {
+    Shape s;
+    int rc = check_desc(desc, &s);
+    if (rc) return rc;
+    if (!mask || !lut || !lut_count) return fail(SPARGE_EINVAL, "NULL argument");
+    if (reinterpret_cast<uintptr_t>(lut) % 4 || reinterpret_cast<uintptr_t>(lut_count) % 4)
+        return fail(SPARGE_EINVAL, "lut and lut_count must be 4-byte aligned");
+    hipError_t e = launch_mask_lut(mask, s, lut, lut_count, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? SPARGE_OK : hip_fail(e, "mask_lut");
+}
+
 int sparge_attn_quantized(const int8_t* Qq, const int8_t* Kq, const float* q_scale, const float* k_scale,
                           const void* V, const sparge_desc* desc, const uint8_t* mask, const float* lambda,
                           float sm_scale, int causal, void* O, uint64_t* stats, void* ws, size_t ws_bytes,

@@ -100,6 +100,8 @@ hipError_t launch_topcdf(const double* logits, const double* sim_q, const double
                          hipStream_t st);
 // V [B,H,N,d] (strided) -> per key block, d rows of 64 key slots in the order the P~V MFMA consumes.
 hipError_t launch_v_tiles(const void* V, const Shape& s, uint16_t* v_tiles, hipStream_t st);
+// lut[b,h,i,:] = the j with mask[b,h,i,j] != 0, ascending, then -1; lut_count[b,h,i] = how many.
+hipError_t launch_mask_lut(const uint8_t* mask, const Shape& s, int32_t* lut, int32_t* lut_count, hipStream_t st);
 // stats[0..n) = 0 (a fill kernel, not a memset node, so callers may capture it in a graph).
 hipError_t launch_zero_stats(unsigned long long* stats, int n, hipStream_t st);
 // The sparse flash loop (accumulates into stats).  queue: ATTN_QUEUE_BYTES of device memory for the item

@@ -424,7 +424,33 @@ __global__ __launch_bounds__(256) void topcdf_wave_kernel(const double* __restri
     }
 }
 
+// The mask as an index list: one wave per mask row compacts the kept block indices with ballots, 64 entries
+// at a time, in ascending order; the rest of the row is -1.
+__global__ __launch_bounds__(256) void mask_lut_kernel(const uint8_t* __restrict__ mask, int Tn, int n_rows,
+                                                       int32_t* __restrict__ lut, int32_t* __restrict__ lut_count) {
+    const int row = blockIdx.x * 4 + static_cast<int>(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (row >= n_rows) return;
+    const uint8_t* m = mask + static_cast<long long>(row) * Tn;
+    int32_t* out = lut + static_cast<long long>(row) * Tn;
+    int n = 0;
+    for (int j0 = 0; j0 < Tn; j0 += 64) {
+        const int j = j0 + lane;
+        const bool keep = j < Tn && m[j] != 0;
+        const unsigned long long bal = __ballot(keep);
+        if (keep) out[n + __popcll(bal & ((1ull << lane) - 1ull))] = j;
+        n += __popcll(bal);
+    }
+    for (int j = n + lane; j < Tn; j += 64) out[j] = -1;
+    if (lane == 0) lut_count[row] = n;
+}
+
 }  // namespace
+
+hipError_t launch_mask_lut(const uint8_t* mask, const Shape& s, int32_t* lut, int32_t* lut_count, hipStream_t st) {
+    const int n_rows = s.B * s.H * s.Tm;
+    hipLaunchKernelGGL(mask_lut_kernel, dim3((n_rows + 3) / 4), dim3(256), 0, st, mask, s.Tn, n_rows, lut, lut_count);
+    return hipGetLastError();
+}
 
 hipError_t launch_logits(const double* pooled_q, const double* ksum_t, const Shape& s, float sm_scale,
                          double* logits, hipStream_t st) {
