@@ -154,6 +154,16 @@ int sparge_attn_quantized(const int8_t* Qq, const int8_t* Kq, const float* q_sca
                           void* O, uint64_t* stats, void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
+ * Diagnostic, host only (no GPU work): the order in which the attention kernel hands out its (batch, head,
+ * Q block) items for this shape.  order: host array of B*H*T_m entries; entry n is (b*H + h)*T_m + i.  The items
+ * are cut into eight contiguous ranges (one per XCD), listed here one after the other; a range hands its items
+ * out in the listed order, the ranges run side by side, and a work-group whose range is empty takes from the
+ * next.  Non-causal: index order.  Causal: per range, first the later (longer) half of every head's Q blocks,
+ * head by head and longest first, then the earlier halves.  The result of a call never depends on this order.
+ */
+int sparge_item_order(const sparge_desc* desc, int causal, int32_t* order /* host, out */);
+
+/*
  * The block mask M_g (Sec. 3.2, Def. 2) as an index list, for callers whose own kernels walk lists of kept
  * blocks: lut int32 [B,H,T_m,T_n], row (b,h,i) holds the j with mask[b,h,i,j] != 0 in ascending order -- the
  * order in which Alg. 1 line 9 visits them -- followed by -1; lut_count int32 [B,H,T_m] their number.

@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     sparge_predict_static,
     STATIC_SCRATCH_BYTES,
     sparge_hilbert_order,
+    sparge_item_order,
     sparge_permute_tokens,
     sparge_quantize,
     sparge_rel_l1,

@@ -60,6 +60,7 @@ def load_library() -> ctypes.CDLL:
     lib.sparge_attn_quantized.argtypes = [vp, vp, vp, vp, vp, dp, vp, f32p, ctypes.c_float, ctypes.c_int, vp, vp,
                                           vp, ctypes.c_size_t, vp]
     lib.sparge_mask_to_lut.argtypes = [vp, dp, vp, vp, vp]
+    lib.sparge_item_order.argtypes = [dp, ctypes.c_int, ctypes.POINTER(ctypes.c_int32)]
     lib.sparge_v_tiles.argtypes = [vp, dp, vp, vp]
     lib.sparge_v_tiles_bytes.argtypes = [dp, ctypes.POINTER(ctypes.c_size_t)]
     lib.sparge_attn_tiled.argtypes = [vp, vp, vp, vp, vp, dp, vp, f32p, ctypes.c_float, ctypes.c_int, vp, vp, vp,
@@ -80,7 +81,7 @@ def load_library() -> ctypes.CDLL:
     lib.sparge_forward.argtypes = [vp, vp, vp, dp, f32p, f32p, f32p, ctypes.c_float, ctypes.c_int, vp, vp, vp, vp,
                                    ctypes.c_size_t, vp]
     for name in ("sparge_workspace_bytes", "sparge_quantize", "sparge_predict", "sparge_attn_quantized",
-                 "sparge_attn", "sparge_forward", "sparge_mask_to_lut", "sparge_v_tiles", "sparge_attn_tiled", "sparge_v_tiles_bytes",
+                 "sparge_attn", "sparge_forward", "sparge_mask_to_lut", "sparge_item_order", "sparge_v_tiles", "sparge_attn_tiled", "sparge_v_tiles_bytes",
                  "sparge_rel_l1", "sparge_tune_workspace_bytes", "sparge_tune", "sparge_hilbert_order",
                  "sparge_permute_tokens"):
         getattr(lib, name).restype = ctypes.c_int
@@ -371,6 +372,16 @@ def sparge_tune(inputs, tau_grid, theta_grid, lambda_grid, l1: float, l2: float,
     return {"tau": list(tau), "theta": list(theta), "lam": list(lam), "sparsity": list(sp), "l1": list(err),
             "stage1": np.array(s1[:]).reshape(len(tau_grid), len(theta_grid), H, 2),
             "stage2": np.array(s2[:n2 * H * 2]).reshape(n2, H, 2)}
+
+
+def sparge_item_order(B: int, H: int, N: int, d: int = 128, causal: bool = False) -> torch.Tensor:
+    """-> int32 [B*H*Tm] (CPU tensor): the attention kernel's items (b*H + h)*Tm + i in hand-out order, the eight
+    ranges one after the other (diagnostic; runs on the host)."""
+    desc = _Desc(B, H, N, d, 1, H * N * d, N * d, d, 0, 0)
+    n = B * H * _blocks(N)[0]
+    buf = (ctypes.c_int32 * max(n, 1))()
+    _check(load_library().sparge_item_order(ctypes.byref(desc), int(causal), buf))
+    return torch.frombuffer(buf, dtype=torch.int32)[:n].clone()
 
 
 def sparge_hilbert_order(T: int, H: int, W: int) -> torch.Tensor:

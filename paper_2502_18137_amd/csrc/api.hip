@@ -6,6 +6,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <algorithm>
 #include <mutex>
 #include <vector>
 
@@ -345,6 +346,24 @@ int sparge_predict_static(const void* Q, const void* K, const sparge_desc* desc,
     if ((rc = static_scratch(&ws))) return rc;
     return sparge_predict(Q, K, desc, tau, theta, sm_scale, causal, mask, sim_q, sim_k, ws,
                           SPARGE_STATIC_SCRATCH_BYTES, hip_stream);
+}
+
+int sparge_item_order(const sparge_desc* desc, int causal, int32_t* order) {
+    Shape s;
+    int rc = check_desc(desc, &s);
+    if (rc) return rc;
+    if (!order) return fail(SPARGE_EINVAL, "order is NULL");
+    const int n_work = s.B * s.H * s.Tm, per_range = (n_work + 7) / 8;
+    int n = 0;
+    for (int y = 0; y < 8; ++y) {
+        const int len = std::min(per_range, n_work - y * per_range);
+        for (int p = 0; p < len; ++p) {
+            const int g = range_item(y * per_range, len, p, s.Tm, causal != 0);
+            const int q = g % s.Tm;
+            order[n++] = g - q + (causal ? s.Tm - 1 - q : q);
+        }
+    }
+    return SPARGE_OK;
 }
 
 int sparge_mask_to_lut(const uint8_t* mask, const sparge_desc* desc, int32_t* lut, int32_t* lut_count, void* hip_stream) {

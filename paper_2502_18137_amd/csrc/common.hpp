@@ -80,6 +80,39 @@ __device__ __forceinline__ uint16_t cvt_to16(float f) {
     return bits;
 }
 
+// Order of the attention kernel's work items.  Items are numbered g = (b H + h) T_m + q; q counts a head's Q
+// blocks from the last one down when the attention is causal (i = T_m - 1 - q: longest rows first), up
+// otherwise (i = q).  They are cut into 8 contiguous ranges of `per_range` items, one per XCD, and a range hands
+// out its items through a counter: p = 0, 1, ... -> the item returned here, for the range that starts at r0 and
+// holds len items.  Non-causal: in index order.  Causal: in two passes over the range's heads, first the longer
+// half of every head's rows (q < T_m - T_m / 2), head by head, then the shorter halves -- so that the items a
+// range ends with are short whichever head they belong to (with whole heads one after the other the long rows
+// of the last head start late and a tenth of the slot time at the causal language shape was an idle tail).
+__host__ __device__ inline int range_item(int r0, int len, int p, int Tm, bool causal) {
+    if (!causal) return r0 + p;
+    const int r1 = r0 + len, longer = Tm - Tm / 2;
+    const int h0 = r0 / Tm, h1 = (r1 - 1) / Tm;
+    for (int pass = 0; pass < 2; ++pass) {
+        const int lo = pass ? longer : 0, hi = pass ? Tm : longer;  // the q of this pass inside a head
+        // the range's first head (it may begin inside it), the whole heads after it, its last head
+        const int a0 = r0 - h0 * Tm > lo ? r0 - h0 * Tm : lo;
+        const int b0 = r1 - h0 * Tm < hi ? r1 - h0 * Tm : hi;
+        const int c0 = b0 > a0 ? b0 - a0 : 0;
+        if (p < c0) return h0 * Tm + a0 + p;
+        p -= c0;
+        if (h1 > h0) {
+            const int whole = (h1 - h0 - 1) * (hi - lo);
+            if (p < whole) return (h0 + 1 + p / (hi - lo)) * Tm + lo + p % (hi - lo);
+            p -= whole;
+            const int b1 = r1 - h1 * Tm < hi ? r1 - h1 * Tm : hi;
+            const int c1 = b1 > lo ? b1 - lo : 0;
+            if (p < c1) return h1 * Tm + lo + p;
+            p -= c1;
+        }
+    }
+    return -1;  // p >= len
+}
+
 // ---- kernel launchers (host functions defined next to their kernels) ----------------------------
 // Block statistics of Q (+ optional INT8 quantization of Q): pooled means, self-similarity.
 hipError_t launch_block_stats_q(const void* Q, const Shape& s, double* pooled_q, double* sim_q,
