@@ -250,17 +250,46 @@ __device__ __forceinline__ void lane_swap(uint32_t a, uint32_t b, uint32_t& a_ou
 // Bitonic sort, descending, of 64 * EPL keys held EPL consecutive ranks per lane.  The stages are
 // instantiated one by one (K: length of the runs being merged, JJ: distance of the pairs), so that every
 // register index, DPP control and swap is a compile-time constant.
+// max / min of two keys read as fp64 numbers: two instructions for a compare-exchange where the 64-bit integer
+// comparison and its four selects take five.  The keys are never NaN or infinite (probabilities <= 1 with an index
+// in the low mantissa bits, or 0), fp64 denormals are not flushed, and the instructions are written out so that
+// the compiler does not canonicalize their inputs first.
+__device__ __forceinline__ void max_min_f64(unsigned long long a, unsigned long long b, unsigned long long& hi,
+                                            unsigned long long& lo) {
+    const double x = __longlong_as_double(static_cast<long long>(a)), y = __longlong_as_double(static_cast<long long>(b));
+    double mx, mn;
+    asm("v_max_f64 %0, %1, %2" : "=v"(mx) : "v"(x), "v"(y));
+    asm("v_min_f64 %0, %1, %2" : "=v"(mn) : "v"(x), "v"(y));
+    hi = static_cast<unsigned long long>(__double_as_longlong(mx));
+    lo = static_cast<unsigned long long>(__double_as_longlong(mn));
+}
+
+// Runs of K >= EPL ranks ascend or descend by lane.  While such runs are merged, the lanes of ascending runs carry
+// their keys with the sign bit set (set_run_sign, once per run length): read as fp64 the keys of every lane then
+// descend the same way, and a pair inside a lane is ordered by max / min without a select.  The comparisons
+// between lanes keep reading the keys as integers; both keys of such a pair carry the same sign bit, so their
+// integer order is the order of the keys themselves.  The last run descends in every lane: the signs end up clear.
+template <int EPL, int K>
+__device__ __forceinline__ void set_run_sign(unsigned long long (&key)[EPL], int lane) {
+    if constexpr (K >= EPL) {
+        const unsigned long long sign = (((lane * EPL) & K) == 0) ? 0ull : 0x8000000000000000ull;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) key[e] = (key[e] & 0x7FFFFFFFFFFFFFFFull) | sign;
+    }
+}
+
 template <int EPL, int K, int JJ>
 __device__ __forceinline__ void bitonic_stage(unsigned long long (&key)[EPL], int lane) {
     if constexpr (JJ < EPL) {  // both members of a pair in this lane
 #pragma unroll
         for (int e = 0; e < EPL; ++e) {
             if (e & JJ) continue;
-            const bool desc = K < EPL ? ((e & K) == 0) : (((lane * EPL) & K) == 0);
-            const unsigned long long a = key[e], b = key[e | JJ];
-            const bool exch = (a > b) != desc;
-            key[e] = exch ? b : a;
-            key[e | JJ] = exch ? a : b;
+            unsigned long long hi, lo;
+            max_min_f64(key[e], key[e | JJ], hi, lo);
+            // short runs: the direction is known per register; long runs: the sign bits make every lane descend
+            const bool desc = K < EPL ? ((e & K) == 0) : true;
+            key[e] = desc ? hi : lo;
+            key[e | JJ] = desc ? lo : hi;
         }
     } else {
         constexpr int LD = JJ / EPL;  // partner lane = lane ^ LD
@@ -309,6 +338,7 @@ __device__ __forceinline__ void bitonic_merge(unsigned long long (&key)[EPL], in
 }
 template <int EPL, int K = 2>
 __device__ __forceinline__ void bitonic_sort(unsigned long long (&key)[EPL], int lane) {
+    set_run_sign<EPL, K>(key, lane);
     bitonic_merge<EPL, K, K / 2>(key, lane);
     if constexpr (K < 64 * EPL) bitonic_sort<EPL, 2 * K>(key, lane);
 }
