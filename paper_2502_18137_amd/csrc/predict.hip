@@ -401,12 +401,15 @@ __global__ __launch_bounds__(256) void topcdf_wave_kernel(const double* __restri
         z += x[e];
     }
     z = wave_sum(z);
+    // (one division per lane; x * (1 / z) is within two roundings of x / z, far inside the band in which a
+    // TopCdf decision counts as undecided)
+    const double rz = z > 0.0 ? 1.0 / z : 0.0;
     double tot = 0.0;
     unsigned long long key[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; ++e) {
         const int j = lane * EPL + e;
-        const double p = (j < s.Tn && z > 0.0) ? x[e] / z : 0.0;
+        const double p = j < s.Tn ? x[e] * rz : 0.0;
         tot += p;
         pval[wave][j] = p;
         flag[wave][j] = 0;
