@@ -23,33 +23,46 @@ __device__ __forceinline__ double shfl_up_f64(double v, int delta) {
     return __hiloint2double(hi, lo);
 }
 
-// Compressed logits as an fp64 matrix product on the matrix cores: a wave computes 16 pooled query rows x 64
+// Compressed logits as an fp64 matrix product on the matrix cores: a wave computes RT x 16 pooled query rows x 64
 // key blocks with v_mfma_f64_16x16x4_f64 (operands: lane = row or column + 16 * k; result register r of a
 // lane = row 4 r + lane / 16, column lane % 16).  The pooled queries are row-major, the key sums
-// transposed ([d][Tn]), so the B operand loads are lane-coalesced; both operands stay L2-resident.
+// transposed ([d][Tn]), so the B operand loads are lane-coalesced; both operands stay L2-resident and go
+// straight from the caches into the operands, RT + 4 loads for 4 RT matrix instructions per step of 4 channels
+// (RT is chosen at launch).
 typedef double v4d __attribute__((ext_vector_type(4)));
-template <int D>
+template <int D, int RT>
 __global__ __launch_bounds__(256) void logits_kernel(const double* __restrict__ pooled_q,
                                                       const double* __restrict__ ksum_t, Shape s,
                                                       double sm_scale, double* __restrict__ logits) {
     const long long bh = blockIdx.z;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int i0 = (blockIdx.y * 4 + wave) * 16, j0 = blockIdx.x * 64;
+    const int i0 = (blockIdx.y * 4 + wave) * 16 * RT, j0 = blockIdx.x * 64;
     if (i0 >= s.Tm) return;
     const int l16 = lane & 15, kk = lane >> 4;
-    const double* qrow = pooled_q + (bh * s.Tm + min(i0 + l16, s.Tm - 1)) * D + kk;   // rows past Tm: a valid row, not stored
+    const double* qrow[RT];
+#pragma unroll
+    for (int u = 0; u < RT; ++u)   // rows past Tm: a valid row, not stored
+        qrow[u] = pooled_q + (bh * s.Tm + min(i0 + 16 * u + l16, s.Tm - 1)) * D + kk;
     const double* kcol[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) kcol[t] = ksum_t + bh * D * s.Tn + (long long)kk * s.Tn + min(j0 + 16 * t + l16, s.Tn - 1);
-    v4d acc[4];
+    v4d acc[RT][4];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) acc[t] = v4d{0.0, 0.0, 0.0, 0.0};
+    for (int u = 0; u < RT; ++u)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) acc[u][t] = v4d{0.0, 0.0, 0.0, 0.0};
 #pragma unroll
     for (int c = 0; c < D; c += 4) {
-        const double a = qrow[c];
+        double a[RT], bcol[4];
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
-            acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, kcol[t][(long long)c * s.Tn], acc[t], 0, 0, 0);
+        for (int u = 0; u < RT; ++u) a[u] = qrow[u][c];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) bcol[t] = kcol[t][(long long)c * s.Tn];
+#pragma unroll
+        for (int u = 0; u < RT; ++u)
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                acc[u][t] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[u], bcol[t], acc[u][t], 0, 0, 0);
     }
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
@@ -57,10 +70,12 @@ __global__ __launch_bounds__(256) void logits_kernel(const double* __restrict__ 
         if (j >= s.Tn) continue;
         const double cnt = static_cast<double>(min(BK, s.N - j * BK));
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int i = i0 + 4 * r + kk;
-            if (i < s.Tm) logits[(bh * s.Tm + i) * s.Tn + j] = sm_scale * (acc[t][r] / cnt);
-        }
+        for (int u = 0; u < RT; ++u)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int i = i0 + 16 * u + 4 * r + kk;
+                if (i < s.Tm) logits[(bh * s.Tm + i) * s.Tn + j] = sm_scale * (acc[u][t][r] / cnt);
+            }
     }
 }
 
@@ -487,10 +502,15 @@ hipError_t launch_mask_lut(const uint8_t* mask, const Shape& s, int32_t* lut, in
 
 hipError_t launch_logits(const double* pooled_q, const double* ksum_t, const Shape& s, float sm_scale,
                          double* logits, hipStream_t st) {
-    dim3 grid((s.Tn + 63) / 64, (s.Tm + 63) / 64, s.B * s.H);
+    // two row tiles of 16 pooled queries per wave where there are enough rows to fill the chip that way
+    // (measured: 55 against 61 us at T_m = 360, 33 against 39 us at T_m = 256 with 32 heads; 18 against 17 us at T_m = 138)
+    const int rt = s.Tm >= 192 ? 2 : 1;
+    dim3 grid((s.Tn + 63) / 64, (s.Tm + 64 * rt - 1) / (64 * rt), s.B * s.H);
     const double scale = sm_scale > 0.f ? static_cast<double>(sm_scale) : 1.0 / sqrt(static_cast<double>(s.d));
-    if (s.d == 64) hipLaunchKernelGGL((logits_kernel<64>), grid, dim3(256), 0, st, pooled_q, ksum_t, s, scale, logits);
-    else hipLaunchKernelGGL((logits_kernel<128>), grid, dim3(256), 0, st, pooled_q, ksum_t, s, scale, logits);
+#define CALL(D, RT) hipLaunchKernelGGL((logits_kernel<D, RT>), grid, dim3(256), 0, st, pooled_q, ksum_t, s, scale, logits)
+    if (s.d == 64) { if (rt == 2) CALL(64, 2); else CALL(64, 1); }
+    else { if (rt == 2) CALL(128, 2); else CALL(128, 1); }
+#undef CALL
     return hipGetLastError();
 }
 
