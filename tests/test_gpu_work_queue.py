@@ -29,6 +29,7 @@ def sp():
     (16, 4224, 128, False, (3, 4)),    # 528 items; two dense heads in one range
     (3, 300, 64, True, (1,)),          # 9 items: fewer than 8 ranges of 2
     (24, 2944, 128, True, (23,)),      # 552 items, causal, the last range holds the dense head
+    (7, 1700, 64, True, (3,)),         # 98 items, causal: ranges of 13 items against heads of 14 Q blocks (two passes per range)
 ])
 def test_unbalanced_heads(sp, H, N, d, causal, dense_heads):
     import torch
